@@ -1,0 +1,147 @@
+/*
+ * libsvdp — decode step of a ReGLU FFN gated by a low-rank SVD sparsity
+ * predictor, for AMD MI355X (gfx950).  C ABI; every pointer named "device" is
+ * a device pointer owned by the caller, the library never frees or keeps it.
+ *
+ * Notation follows the paper: d = hidden size, D = intermediate size,
+ * r = predictor rank, x in R^d a decode token, W_gate, W_up in R^{D x d},
+ * W_down in R^{d x D} (Sec. 3).  The predictor A B x + b of Sec. 4.1, eq. (2)
+ * is passed in row-vector form: P = B^T (d x r), Q = A (D x r), so that the
+ * scores are s = (x P) Q^T + b.
+ *
+ * Common rules for every call that takes a stream:
+ *  - asynchronous on `stream` (a hipStream_t passed as void*, NULL = default
+ *    stream); the call never synchronises, never allocates device memory and
+ *    never copies device data to the host, so it can be captured in a HIP graph;
+ *  - arguments are validated on the host first; on any error nothing is
+ *    enqueued and a status other than SVDP_OK is returned;
+ *  - `ws` is a device scratch buffer of at least svdp_workspace_bytes() bytes,
+ *    256-byte aligned, owned by the caller; its contents are undefined between
+ *    calls; two calls that may overlap in time need distinct workspaces;
+ *  - B is the number of tokens decoded together, 1 <= B <= SVDP_MAX_BATCH; all
+ *    tokens of a batch share ONE mask (the union of their masks) and one index
+ *    list, and every token is computed exactly over that list;
+ *  - results are deterministic: floating-point sums are formed in a fixed
+ *    order that depends only on the shapes and on the index list (no
+ *    floating-point atomics, as in the paper's App. C down projection).
+ *
+ * Shape limits (else SVDP_ERR_UNSUPPORTED): D % 64 == 0, and with
+ * e = 4 (fp32) or 8 (bf16) elements per 16 bytes: d % e == 0, r % e == 0,
+ * r <= 1024 (fp32) or 2048 (bf16), d <= 16384.  Every matrix pointer must be 16-byte aligned.
+ */
+#ifndef SVDP_H
+#define SVDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SVDP_MAX_BATCH 8
+
+typedef enum {
+    SVDP_OK = 0,
+    SVDP_ERR_INVALID_ARG = 1,  /* null pointer, bad size, misaligned pointer   */
+    SVDP_ERR_UNSUPPORTED = 2,  /* shape or dtype outside the limits above       */
+    SVDP_ERR_WORKSPACE = 3,    /* ws is NULL, misaligned or too small           */
+    SVDP_ERR_HIP = 4           /* the HIP runtime refused a launch              */
+} svdp_status;
+
+typedef enum {
+    SVDP_F32 = 0,  /* IEEE binary32 */
+    SVDP_BF16 = 1  /* bfloat16 bit patterns (upper 16 bits of a binary32) */
+} svdp_dtype;
+
+/* Flags of svdp_layer.flags */
+enum {
+    /* dReLU variant (paper Sec. 5.1, eq. 6): ReLU is applied to the up branch too. */
+    SVDP_FLAG_DRELU = 1u,
+    /* Sequential pipeline (paper Sec. 4.2, "Gate/up execution order"): after the
+     * gate product of a predicted-active neuron is known, its W_down row is
+     * skipped when the gate is <= 0 for every token of the batch.  The output is
+     * unchanged (such a neuron contributes exactly zero).                         */
+    SVDP_FLAG_REVALIDATE = 2u
+};
+
+/* One FFN layer with its predictor.  All pointers are device pointers.
+ * Storage precision policy (paper App. C, "Precision"): weights, predictor
+ * factors and tokens are stored in `wdtype`; all arithmetic, the rank-r
+ * intermediate t = x P, the scores and y are fp32.                              */
+typedef struct svdp_layer {
+    int32_t d, D, r;
+    int32_t wdtype;        /* svdp_dtype of P, Q, W_gate, W_up, W_downT and of x          */
+    const void *P;         /* [d][r] row-major                                            */
+    const void *Q;         /* [D][r] row-major                                            */
+    const float *b;        /* [D] fp32 bias (= minus the calibrated threshold, Alg. 2)    */
+    const void *W_gate;    /* [D][d] row-major: row i = neuron i                          */
+    const void *W_up;      /* [D][d] row-major                                            */
+    const void *W_downT;   /* [D][d] row-major: row i = column i of W_down (the paper's
+                              column-major W_down, App. C "Memory")                       */
+    uint32_t flags;        /* SVDP_FLAG_*                                                 */
+} svdp_layer;
+
+/* Bytes of device scratch any call below needs for this layer and up to
+ * max_batch tokens.  Host-only, pure.  Returns 0 if the layer is unsupported.   */
+size_t svdp_workspace_bytes(const svdp_layer *layer, int32_t max_batch);
+
+/* Predictor scores (Sec. 4.1, eq. 2, before the step function; first line of
+ * Alg. 3):  s[t][i] = sum_k (sum_j x[t][j] P[j][k]) Q[i][k] + b[i].
+ * x: device [B][d] in layer->wdtype.  s: device [B][D] fp32, fully written.     */
+svdp_status svdp_predict(const svdp_layer *layer, const void *x, int32_t B,
+                         float *s, void *ws, size_t ws_bytes, void *stream);
+
+/* Mask and index list (step function H of eq. 2; Alg. 4's nonzero):
+ * neuron i is active iff s[t][i] > 0 (strictly; NaN is inactive) for at least
+ * one token t < B.
+ * s: device [B][D] fp32.  mask: device [D/64] 64-bit words, bit j of word k is
+ * neuron 64k+j, fully written.  idx: device [D] int32, receives the active neurons
+ * in ascending order in idx[0..nnz), the rest is left untouched.  nnz: device
+ * [1] int32.  Needs no workspace.                                               */
+svdp_status svdp_compact(const float *s, int32_t B, int32_t D, uint64_t *mask,
+                         int32_t *idx, int32_t *nnz, void *stream);
+
+/* Sparse ReGLU FFN over an index list (Sec. 3; Alg. 3's three kernels / Alg. 4):
+ *   y[t][:] = sum_{n < nnz} ReLU(W_gate[i_n]·x[t]) * (W_up[i_n]·x[t]) * W_downT[i_n][:],
+ * i_n = idx[n].  Only the listed rows of the three matrices are read.
+ * idx: device int32, entries in [0, D), ascending not required but duplicates
+ * are summed twice.  nnz: device [1] int32 with 0 <= *nnz <= D (read on the
+ * device, never on the host).  y: device [B][d] fp32, fully written (zeros
+ * when *nnz == 0).                                                              */
+svdp_status svdp_sparse_ffn(const svdp_layer *layer, const void *x, int32_t B,
+                            const int32_t *idx, const int32_t *nnz, float *y,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* Dense ReGLU FFN (Sec. 3, eq. 1) over all D neurons: the same-GPU baseline
+ * the sparse step is compared with.  y: device [B][d] fp32.                     */
+svdp_status svdp_dense_ffn(const svdp_layer *layer, const void *x, int32_t B,
+                           float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* The whole decode step of Alg. 3 for one batch: scores, union mask, index
+ * list, sparse FFN.  Equivalent to svdp_predict + svdp_compact +
+ * svdp_sparse_ffn without materialising the scores.
+ * mask_out [D/64], idx_out [D], nnz_out [1]: device, each nullable; when given
+ * they receive what svdp_compact would have produced.  y: device [B][d] fp32.   */
+svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, float *y,
+                          uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* Glue between stacked layers used by the stacked benchmark (not from the
+ * paper): v = x + y; x_next = v / sqrt(mean(v^2) + eps) + shift, rounded to
+ * `dtype`.  x: device [d] in `dtype`; y: device [d] fp32; shift: device [d]
+ * fp32; x_next: device [d] in `dtype` (may alias x).                            */
+svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift,
+                            int32_t d, int32_t dtype, float eps, void *x_next,
+                            void *stream);
+
+/* Static string for a status code.  Never NULL. */
+const char *svdp_status_string(svdp_status st);
+
+/* Library version, "major.minor". */
+const char *svdp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVDP_H */

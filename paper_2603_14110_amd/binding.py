@@ -1,0 +1,224 @@
+"""Thin ctypes binding over ``libsvdp.so`` (declared in ``include/svdp.h``).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream, every step of the path runs in the library's kernels.  There is no CPU
+or eager fallback: if the library has not been built, ``lib()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch  # imported before the library so both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsvdp.so")
+
+SVDP_F32, SVDP_BF16 = 0, 1
+FLAG_DRELU, FLAG_REVALIDATE = 1, 2
+MAX_BATCH = 8
+
+EXPORTS = [
+    "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
+    "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version",
+]
+
+
+class SvdpError(RuntimeError):
+    pass
+
+
+class svdp_layer(ctypes.Structure):
+    _fields_ = [
+        ("d", ctypes.c_int32), ("D", ctypes.c_int32), ("r", ctypes.c_int32), ("wdtype", ctypes.c_int32),
+        ("P", ctypes.c_void_p), ("Q", ctypes.c_void_p), ("b", ctypes.c_void_p),
+        ("W_gate", ctypes.c_void_p), ("W_up", ctypes.c_void_p), ("W_downT", ctypes.c_void_p),
+        ("flags", ctypes.c_uint32),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library; raises SvdpError when it is missing (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise SvdpError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lp = ctypes.POINTER(svdp_layer)
+    L.svdp_workspace_bytes.argtypes = [lp, i32]
+    L.svdp_workspace_bytes.restype = sz
+    L.svdp_predict.argtypes = [lp, vp, i32, vp, vp, sz, vp]
+    L.svdp_compact.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    L.svdp_sparse_ffn.argtypes = [lp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.svdp_dense_ffn.argtypes = [lp, vp, i32, vp, vp, sz, vp]
+    L.svdp_ffn_step.argtypes = [lp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.svdp_stack_glue.argtypes = [vp, vp, vp, i32, i32, ctypes.c_float, vp, vp]
+    for n in ("svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn", "svdp_ffn_step",
+              "svdp_stack_glue"):
+        getattr(L, n).restype = ctypes.c_int
+    L.svdp_status_string.argtypes = [ctypes.c_int]
+    L.svdp_status_string.restype = ctypes.c_char_p
+    L.svdp_version.argtypes = []
+    L.svdp_version.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(st: int, what: str) -> None:
+    if st != 0:
+        raise SvdpError(f"{what}: {lib().svdp_status_string(st).decode()} (status {st})")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not (t.is_cuda and t.is_contiguous()):
+        raise SvdpError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Storage array from ``synth`` (float32, or uint16 bf16 bits) -> device tensor."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+class DeviceLayer:
+    """Device-resident layer: owns the tensors and the C struct that points at them."""
+
+    def __init__(self, P, Q, b, W_gate, W_up, W_downT, flags: int = 0):
+        self.tensors = dict(P=P, Q=Q, b=b, W_gate=W_gate, W_up=W_up, W_downT=W_downT)
+        wd = W_gate.dtype
+        if wd not in (torch.float32, torch.bfloat16):
+            raise SvdpError(f"unsupported weight dtype {wd}")
+        for k, t in self.tensors.items():
+            if not (t.is_cuda and t.is_contiguous()):
+                raise SvdpError(f"{k}: expected a contiguous device tensor")
+            if k != "b" and t.dtype != wd:
+                raise SvdpError(f"{k}: dtype {t.dtype} differs from W_gate's {wd}")
+        if b.dtype != torch.float32:
+            raise SvdpError("b must be float32")
+        self.D, self.d = W_gate.shape
+        self.r = P.shape[1]
+        assert P.shape == (self.d, self.r) and Q.shape == (self.D, self.r) and b.shape == (self.D,)
+        assert W_up.shape == (self.D, self.d) and W_downT.shape == (self.D, self.d)
+        self.dtype = wd
+        self.c = svdp_layer(self.d, self.D, self.r, SVDP_BF16 if wd == torch.bfloat16 else SVDP_F32,
+                            P.data_ptr(), Q.data_ptr(), b.data_ptr(), W_gate.data_ptr(), W_up.data_ptr(),
+                            W_downT.data_ptr(), flags)
+        self._ws = {}
+
+    @classmethod
+    def from_synth(cls, layer, flags: int = 0, device="cuda") -> "DeviceLayer":
+        dt = layer.spec.dtype
+        g = lambda name: to_device(getattr(layer, name), dt, device)
+        return cls(g("P"), g("Q"), torch.from_numpy(layer.b).to(device), g("W_gate"), g("W_up"), g("W_downT"), flags)
+
+    def clone(self) -> "DeviceLayer":
+        """A copy at fresh device addresses (used to defeat cache residency when timing)."""
+        t = {k: v.clone() for k, v in self.tensors.items()}
+        return DeviceLayer(t["P"], t["Q"], t["b"], t["W_gate"], t["W_up"], t["W_downT"], self.c.flags)
+
+    def with_flags(self, flags: int) -> "DeviceLayer":
+        t = self.tensors
+        return DeviceLayer(t["P"], t["Q"], t["b"], t["W_gate"], t["W_up"], t["W_downT"], flags)
+
+    def workspace(self, max_batch: int = 1) -> torch.Tensor:
+        key = int(max_batch)
+        if key not in self._ws:
+            n = workspace_bytes(self, max_batch)
+            self._ws[key] = torch.empty(n, dtype=torch.uint8, device=self.tensors["P"].device)
+        return self._ws[key]
+
+
+def workspace_bytes(layer: DeviceLayer, max_batch: int) -> int:
+    n = lib().svdp_workspace_bytes(ctypes.byref(layer.c), int(max_batch))
+    if n == 0:
+        raise SvdpError("svdp_workspace_bytes: unsupported layer or batch")
+    return int(n)
+
+
+def _x2(layer: DeviceLayer, x: torch.Tensor) -> Tuple[torch.Tensor, int]:
+    if x.dim() == 1:
+        x = x[None, :]
+    if x.dtype != layer.dtype or x.shape[1] != layer.d:
+        raise SvdpError(f"x: expected [B][{layer.d}] of {layer.dtype}, got {tuple(x.shape)} {x.dtype}")
+    return x, x.shape[0]
+
+
+def predict(layer: DeviceLayer, x: torch.Tensor, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    x, B = _x2(layer, x)
+    ws = layer.workspace(B) if ws is None else ws
+    s = torch.empty((B, layer.D), dtype=torch.float32, device=x.device)
+    _check(lib().svdp_predict(ctypes.byref(layer.c), _ptr(x), B, _ptr(s), _ptr(ws), ws.numel(), _stream()),
+           "svdp_predict")
+    return s
+
+
+def compact(s: torch.Tensor):
+    """Returns (mask int64 [D/64], idx int32 [D], nnz int32 [1]) device tensors."""
+    if s.dim() == 1:
+        s = s[None, :]
+    B, D = s.shape
+    mask = torch.empty(max(D // 64, 1), dtype=torch.int64, device=s.device)
+    idx = torch.full((D,), -1, dtype=torch.int32, device=s.device)
+    nnz = torch.empty(1, dtype=torch.int32, device=s.device)
+    _check(lib().svdp_compact(_ptr(s), B, D, _ptr(mask), _ptr(idx), _ptr(nnz), _stream()), "svdp_compact")
+    return mask, idx, nnz
+
+
+def sparse_ffn(layer: DeviceLayer, x: torch.Tensor, idx: torch.Tensor, nnz: torch.Tensor,
+               ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    x, B = _x2(layer, x)
+    ws = layer.workspace(B) if ws is None else ws
+    y = torch.empty((B, layer.d), dtype=torch.float32, device=x.device) if out is None else out
+    _check(lib().svdp_sparse_ffn(ctypes.byref(layer.c), _ptr(x), B, _ptr(idx), _ptr(nnz), _ptr(y), _ptr(ws),
+                                 ws.numel(), _stream()), "svdp_sparse_ffn")
+    return y
+
+
+def dense_ffn(layer: DeviceLayer, x: torch.Tensor, ws: Optional[torch.Tensor] = None,
+              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    x, B = _x2(layer, x)
+    ws = layer.workspace(B) if ws is None else ws
+    y = torch.empty((B, layer.d), dtype=torch.float32, device=x.device) if out is None else out
+    _check(lib().svdp_dense_ffn(ctypes.byref(layer.c), _ptr(x), B, _ptr(y), _ptr(ws), ws.numel(), _stream()),
+           "svdp_dense_ffn")
+    return y
+
+
+def ffn_step(layer: DeviceLayer, x: torch.Tensor, ws: Optional[torch.Tensor] = None,
+             out: Optional[torch.Tensor] = None, mask: Optional[torch.Tensor] = None,
+             idx: Optional[torch.Tensor] = None, nnz: Optional[torch.Tensor] = None) -> torch.Tensor:
+    x, B = _x2(layer, x)
+    ws = layer.workspace(B) if ws is None else ws
+    y = torch.empty((B, layer.d), dtype=torch.float32, device=x.device) if out is None else out
+    _check(lib().svdp_ffn_step(ctypes.byref(layer.c), _ptr(x), B, _ptr(y), _ptr(mask), _ptr(idx), _ptr(nnz),
+                               _ptr(ws), ws.numel(), _stream()), "svdp_ffn_step")
+    return y
+
+
+def stack_glue(x: torch.Tensor, y: torch.Tensor, shift: torch.Tensor, eps: float = 1e-6,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    d = x.numel()
+    out = torch.empty_like(x) if out is None else out
+    dt = SVDP_BF16 if x.dtype == torch.bfloat16 else SVDP_F32
+    _check(lib().svdp_stack_glue(_ptr(x), _ptr(y), _ptr(shift), d, dt, float(eps), _ptr(out), _stream()),
+           "svdp_stack_glue")
+    return out
+
+
+def version() -> str:
+    return lib().svdp_version().decode()

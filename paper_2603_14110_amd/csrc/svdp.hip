@@ -1,0 +1,338 @@
+// C-ABI entry points of libsvdp (see include/svdp.h): host-side validation,
+// workspace carving and kernel launches.  No allocation, no synchronisation.
+#include "../../include/svdp.h"
+
+#include <hip/hip_runtime.h>
+
+#include "svdp_kernels.h"
+
+namespace {
+
+using namespace svdp;
+
+constexpr int XP_MAX_BLOCKS = 64;     // stage-1 row slabs of P
+constexpr int ROWS_GRID = 512;        // k_rows blocks (chunks of the row list)
+constexpr size_t ALIGN = 256;
+
+inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+inline int nb_of(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : 8; }
+inline int elem_bytes(int dt) { return dt == SVDP_F32 ? 4 : 2; }
+inline int vec_of(int dt) { return dt == SVDP_F32 ? 4 : 8; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+svdp_status check_shape(int d, int D, int r, int dt)
+{
+    if (dt != SVDP_F32 && dt != SVDP_BF16) return SVDP_ERR_UNSUPPORTED;
+    if (d <= 0 || D <= 0 || r <= 0) return SVDP_ERR_INVALID_ARG;
+    const int e = vec_of(dt);
+    if (D % 64 != 0 || d % e != 0 || r % e != 0) return SVDP_ERR_UNSUPPORTED;
+    if (r / e > XP_THREADS || r > 2048 || d > 16384) return SVDP_ERR_UNSUPPORTED;
+    return SVDP_OK;
+}
+
+svdp_status check_layer(const svdp_layer *L, bool need_pred, bool need_ffn)
+{
+    if (L == nullptr) return SVDP_ERR_INVALID_ARG;
+    const svdp_status st = check_shape(L->d, L->D, L->r, L->wdtype);
+    if (st != SVDP_OK) return st;
+    if (need_pred && (!L->P || !L->Q || !L->b || !aligned16(L->P) || !aligned16(L->Q) ||
+                      (reinterpret_cast<uintptr_t>(L->b) & 3u)))
+        return SVDP_ERR_INVALID_ARG;
+    if (need_ffn && (!L->W_gate || !L->W_up || !L->W_downT || !aligned16(L->W_gate) ||
+                     !aligned16(L->W_up) || !aligned16(L->W_downT)))
+        return SVDP_ERR_INVALID_ARG;
+    if (L->flags & ~(uint32_t)(SVDP_FLAG_DRELU | SVDP_FLAG_REVALIDATE)) return SVDP_ERR_INVALID_ARG;
+    return SVDP_OK;
+}
+
+// Workspace layout (all offsets 256-byte aligned):
+//   tpart [XP_MAX_BLOCKS][NB][r] f32 | mask [D/64] u64 | idx [D] i32 | nnz i32 | ypart [ROWS_GRID][NB][d] f32
+struct Workspace {
+    float *tpart;
+    uint64_t *mask;
+    int32_t *idx;
+    int32_t *nnz;
+    float *ypart;
+    size_t bytes;
+};
+
+Workspace carve(void *base, int d, int D, int r, int NB)
+{
+    Workspace w;
+    char *p = static_cast<char *>(base);
+    size_t off = 0;
+    w.tpart = reinterpret_cast<float *>(p + off);
+    off += align_up((size_t)XP_MAX_BLOCKS * NB * r * 4);
+    w.mask = reinterpret_cast<uint64_t *>(p + off);
+    off += align_up((size_t)D / 64 * 8);
+    w.idx = reinterpret_cast<int32_t *>(p + off);
+    off += align_up((size_t)D * 4);
+    w.nnz = reinterpret_cast<int32_t *>(p + off);
+    off += ALIGN;
+    w.ypart = reinterpret_cast<float *>(p + off);
+    off += align_up((size_t)ROWS_GRID * NB * d * 4);
+    w.bytes = off;
+    return w;
+}
+
+svdp_status check_ws(const svdp_layer *L, int B, void *ws, size_t ws_bytes, Workspace *out)
+{
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1))) return SVDP_ERR_WORKSPACE;
+    *out = carve(ws, L->d, L->D, L->r, nb_of(B));
+    if (ws_bytes < out->bytes) return SVDP_ERR_WORKSPACE;
+    return SVDP_OK;
+}
+
+// Dynamic LDS above the default limit has to be enabled per kernel once.
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes, int *granted)
+{
+    if ((int)bytes <= *granted) return hipSuccess;
+    if (bytes > 160 * 1024) return hipErrorInvalidValue;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) *granted = (int)bytes;
+    return e;
+}
+
+inline svdp_status hip_status(hipError_t e)
+{
+    if (e == hipSuccess) e = hipGetLastError();
+    else (void)hipGetLastError();
+    return e == hipSuccess ? SVDP_OK : SVDP_ERR_HIP;
+}
+
+// ---- launch helpers, one per kernel, templated on storage type and batch capacity ----
+
+template <typename W, int NB>
+svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, int *nt_out, hipStream_t st)
+{
+    constexpr int VEC = Elem<W>::VEC;
+    const int d = L->d, r = L->r;
+    int nt = d / 64;
+    nt = nt < 1 ? 1 : (nt > XP_MAX_BLOCKS ? XP_MAX_BLOCKS : nt);
+    const int rows = (d + nt - 1) / nt;
+    nt = (d + rows - 1) / rows;
+    const size_t lds = ((size_t)NB * rows + (size_t)XP_THREADS * VEC * NB) * 4;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_xP<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_xP<W, NB>), dim3(nt), dim3(XP_THREADS), lds, st, static_cast<const W *>(L->P),
+                       static_cast<const W *>(x), B, d, r, rows, tpart);
+    *nt_out = nt;
+    return hip_status(hipSuccess);
+}
+
+template <typename W, int NB>
+svdp_status launch_scores(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
+                          uint64_t *mask_out, hipStream_t st)
+{
+    constexpr int VEC = Elem<W>::VEC;
+    const int cg = L->r / VEC;
+    int lpr_log2 = 0;
+    while ((1 << lpr_log2) < cg && lpr_log2 < 6) ++lpr_log2;
+    const size_t lds = ((size_t)NB * L->r + (size_t)NB * SC_SLAB) * 4;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_scores<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_scores<W, NB>), dim3(L->D / SC_SLAB), dim3(SC_THREADS), lds, st,
+                       static_cast<const W *>(L->Q), L->b, tpart, nt, B, L->D, L->r, lpr_log2, s_out, mask_out);
+    return hip_status(hipSuccess);
+}
+
+template <typename W, int NB, bool DENSE>
+svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const int32_t *idx, const int32_t *nnz,
+                        float *ypart, float *y, hipStream_t st)
+{
+    const int d = L->d, D = L->D;
+    const int max_chunk = (D + ROWS_GRID - 1) / ROWS_GRID;
+    const size_t lds = ((size_t)NB * d + (size_t)NB * max_chunk) * 4;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_rows<W, NB, DENSE>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_rows<W, NB, DENSE>), dim3(ROWS_GRID), dim3(ROWS_THREADS), lds, st,
+                       static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
+                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, idx, nnz,
+                       max_chunk, L->flags, ypart);
+    svdp_status s = hip_status(hipSuccess);
+    if (s != SVDP_OK) return s;
+    const int threads = B * (d / 4);
+    hipLaunchKernelGGL(k_reduce_y, dim3((threads + 255) / 256), dim3(256), 0, st, ypart,
+                       DENSE ? nullptr : nnz, D, D, ROWS_GRID, NB, B, d, y);
+    return hip_status(hipSuccess);
+}
+
+svdp_status launch_compact(const uint64_t *mask, int D, int32_t *idx, int32_t *nnz, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(SCAN_THREADS), 0, st, mask, D / 64, idx, nnz);
+    return hip_status(hipSuccess);
+}
+
+// dispatch on (dtype, batch capacity)
+#define SVDP_DISPATCH(dt, NBv, CALL)                                                         \
+    do {                                                                                     \
+        if ((dt) == SVDP_F32) {                                                              \
+            using W = float;                                                                 \
+            switch (NBv) {                                                                   \
+            case 1: { constexpr int NB = 1; return CALL; }                                   \
+            case 2: { constexpr int NB = 2; return CALL; }                                   \
+            case 4: { constexpr int NB = 4; return CALL; }                                   \
+            default: { constexpr int NB = 8; return CALL; }                                  \
+            }                                                                                \
+        } else {                                                                             \
+            using W = bf16;                                                                  \
+            switch (NBv) {                                                                   \
+            case 1: { constexpr int NB = 1; return CALL; }                                   \
+            case 2: { constexpr int NB = 2; return CALL; }                                   \
+            case 4: { constexpr int NB = 4; return CALL; }                                   \
+            default: { constexpr int NB = 8; return CALL; }                                  \
+            }                                                                                \
+        }                                                                                    \
+    } while (0)
+
+template <typename W, int NB>
+svdp_status run_predict(const svdp_layer *L, const void *x, int B, float *s, uint64_t *mask, const Workspace &w,
+                        hipStream_t st)
+{
+    int nt = 0;
+    svdp_status e = launch_xP<W, NB>(L, x, B, w.tpart, &nt, st);
+    if (e != SVDP_OK) return e;
+    return launch_scores<W, NB>(L, w.tpart, nt, B, s, mask, st);
+}
+
+template <typename W, int NB>
+svdp_status run_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
+                     int32_t *nnz_out, const Workspace &w, hipStream_t st)
+{
+    uint64_t *mask = mask_out ? mask_out : w.mask;
+    int32_t *idx = idx_out ? idx_out : w.idx;
+    int32_t *nnz = nnz_out ? nnz_out : w.nnz;
+    svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st);
+    if (e != SVDP_OK) return e;
+    e = launch_compact(mask, L->D, idx, nnz, st);
+    if (e != SVDP_OK) return e;
+    return launch_rows<W, NB, false>(L, x, B, idx, nnz, w.ypart, y, st);
+}
+
+svdp_status dispatch_predict(const svdp_layer *L, const void *x, int B, float *s, const Workspace &w, hipStream_t st)
+{
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (run_predict<W, NB>(L, x, B, s, nullptr, w, st)));
+}
+svdp_status dispatch_sparse(const svdp_layer *L, const void *x, int B, const int32_t *idx, const int32_t *nnz,
+                            float *y, const Workspace &w, hipStream_t st)
+{
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, false>(L, x, B, idx, nnz, w.ypart, y, st)));
+}
+svdp_status dispatch_dense(const svdp_layer *L, const void *x, int B, float *y, const Workspace &w, hipStream_t st)
+{
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, true>(L, x, B, nullptr, nullptr, w.ypart, y, st)));
+}
+svdp_status dispatch_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out,
+                          int32_t *idx_out, int32_t *nnz_out, const Workspace &w, hipStream_t st)
+{
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (run_step<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, st)));
+}
+
+inline bool bad_batch(int B) { return B < 1 || B > SVDP_MAX_BATCH; }
+
+}  // namespace
+
+extern "C" {
+
+size_t svdp_workspace_bytes(const svdp_layer *layer, int32_t max_batch)
+{
+    if (layer == nullptr || bad_batch(max_batch)) return 0;
+    if (check_shape(layer->d, layer->D, layer->r, layer->wdtype) != SVDP_OK) return 0;
+    return carve(nullptr, layer->d, layer->D, layer->r, nb_of(max_batch)).bytes;
+}
+
+svdp_status svdp_predict(const svdp_layer *layer, const void *x, int32_t B, float *s, void *ws, size_t ws_bytes,
+                         void *stream)
+{
+    svdp_status st = check_layer(layer, true, false);
+    if (st != SVDP_OK) return st;
+    if (x == nullptr || s == nullptr || bad_batch(B) || !aligned16(x)) return SVDP_ERR_INVALID_ARG;
+    Workspace w;
+    st = check_ws(layer, B, ws, ws_bytes, &w);
+    if (st != SVDP_OK) return st;
+    return dispatch_predict(layer, x, B, s, w, static_cast<hipStream_t>(stream));
+}
+
+svdp_status svdp_compact(const float *s, int32_t B, int32_t D, uint64_t *mask, int32_t *idx, int32_t *nnz,
+                         void *stream)
+{
+    if (s == nullptr || mask == nullptr || idx == nullptr || nnz == nullptr || bad_batch(B) || D <= 0) return SVDP_ERR_INVALID_ARG;
+    if (D % 64 != 0) return SVDP_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_mask_from_scores, dim3((D / 64 + 3) / 4), dim3(256), 0, st, s, B, D, mask);
+    svdp_status e = hip_status(hipSuccess);
+    if (e != SVDP_OK) return e;
+    return launch_compact(mask, D, idx, nnz, st);
+}
+
+svdp_status svdp_sparse_ffn(const svdp_layer *layer, const void *x, int32_t B, const int32_t *idx,
+                            const int32_t *nnz, float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    svdp_status st = check_layer(layer, false, true);
+    if (st != SVDP_OK) return st;
+    if (x == nullptr || y == nullptr || idx == nullptr || nnz == nullptr || bad_batch(B) || !aligned16(x) ||
+        !aligned16(y))
+        return SVDP_ERR_INVALID_ARG;
+    Workspace w;
+    st = check_ws(layer, B, ws, ws_bytes, &w);
+    if (st != SVDP_OK) return st;
+    return dispatch_sparse(layer, x, B, idx, nnz, y, w, static_cast<hipStream_t>(stream));
+}
+
+svdp_status svdp_dense_ffn(const svdp_layer *layer, const void *x, int32_t B, float *y, void *ws, size_t ws_bytes,
+                           void *stream)
+{
+    svdp_status st = check_layer(layer, false, true);
+    if (st != SVDP_OK) return st;
+    if (x == nullptr || y == nullptr || bad_batch(B) || !aligned16(x) || !aligned16(y)) return SVDP_ERR_INVALID_ARG;
+    Workspace w;
+    st = check_ws(layer, B, ws, ws_bytes, &w);
+    if (st != SVDP_OK) return st;
+    return dispatch_dense(layer, x, B, y, w, static_cast<hipStream_t>(stream));
+}
+
+svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, float *y, uint64_t *mask_out,
+                          int32_t *idx_out, int32_t *nnz_out, void *ws, size_t ws_bytes, void *stream)
+{
+    svdp_status st = check_layer(layer, true, true);
+    if (st != SVDP_OK) return st;
+    if (x == nullptr || y == nullptr || bad_batch(B) || !aligned16(x) || !aligned16(y)) return SVDP_ERR_INVALID_ARG;
+    Workspace w;
+    st = check_ws(layer, B, ws, ws_bytes, &w);
+    if (st != SVDP_OK) return st;
+    return dispatch_step(layer, x, B, y, mask_out, idx_out, nnz_out, w, static_cast<hipStream_t>(stream));
+}
+
+svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift, int32_t d, int32_t dtype, float eps,
+                            void *x_next, void *stream)
+{
+    if (x == nullptr || y == nullptr || shift == nullptr || x_next == nullptr || d <= 0) return SVDP_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == SVDP_F32)
+        hipLaunchKernelGGL(k_stack_glue<float>, dim3(1), dim3(1024), 0, st, static_cast<const float *>(x), y, shift,
+                           d, eps, static_cast<float *>(x_next));
+    else if (dtype == SVDP_BF16)
+        hipLaunchKernelGGL(k_stack_glue<bf16>, dim3(1), dim3(1024), 0, st, static_cast<const bf16 *>(x), y, shift, d,
+                           eps, static_cast<bf16 *>(x_next));
+    else
+        return SVDP_ERR_UNSUPPORTED;
+    return hip_status(hipSuccess);
+}
+
+const char *svdp_status_string(svdp_status st)
+{
+    switch (st) {
+    case SVDP_OK: return "ok";
+    case SVDP_ERR_INVALID_ARG: return "invalid argument";
+    case SVDP_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case SVDP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SVDP_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char *svdp_version(void) { return "0.1"; }
+
+}  // extern "C"

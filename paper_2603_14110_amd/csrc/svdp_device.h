@@ -1,0 +1,96 @@
+// Device-side helpers for the gfx950 kernels: 16-byte weight loads widened to
+// fp32, wave64 reductions on DPP, bf16 <-> fp32 bit conversions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace svdp {
+
+// bfloat16 storage element (bit pattern only; all arithmetic is fp32, the
+// "full precision registers, half precision memory" policy of the paper's App. C).
+struct bf16 {
+    uint16_t bits;
+};
+
+template <typename W>
+struct Elem;
+template <>
+struct Elem<float> {
+    static constexpr int VEC = 4;   // elements per 16-byte load
+    static constexpr int BYTES = 4;
+};
+template <>
+struct Elem<bf16> {
+    static constexpr int VEC = 8;
+    static constexpr int BYTES = 2;
+};
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return __uint_as_float(((uint32_t)v.bits) << 16); }
+
+// fp32 -> storage element, round-to-nearest-even (NaN stays NaN).
+__device__ __forceinline__ void from_f32(float v, float *out) { *out = v; }
+__device__ __forceinline__ void from_f32(float v, bf16 *out)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {
+        out->bits = (uint16_t)((u >> 16) | 0x40u);
+    } else {
+        u += 0x7fffu + ((u >> 16) & 1u);
+        out->bits = (uint16_t)(u >> 16);
+    }
+}
+
+// One 16-byte load of VEC consecutive elements, widened to fp32.  p must be
+// 16-byte aligned.
+__device__ __forceinline__ void load_vec(const float *p, float (&v)[4])
+{
+    const float4 q = *reinterpret_cast<const float4 *>(p);
+    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+}
+__device__ __forceinline__ void load_vec(const bf16 *p, float (&v)[8])
+{
+    const uint4 q = *reinterpret_cast<const uint4 *>(p);
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+    v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 64 lanes of a wave in a fixed order; the result is uniform.
+// Four DPP steps give every lane the sum of its row of 16, then the four row
+// sums are read out and added in lane order.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);   // row_half_mirror
+    v += dpp_move<0x140>(v);   // row_mirror
+    const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (a + b) + (c + d);
+}
+
+// Sum over aligned groups of 2^LOG2 consecutive lanes; every lane of a group
+// gets the group's sum.  Butterfly order, fixed.
+__device__ __forceinline__ float group_sum(float v, int log2_lanes)
+{
+    if (log2_lanes >= 1) v += dpp_move<0xB1>(v);
+    if (log2_lanes >= 2) v += dpp_move<0x4E>(v);
+    if (log2_lanes >= 3) v += dpp_move<0x141>(v);
+    if (log2_lanes >= 4) v += dpp_move<0x140>(v);
+    if (log2_lanes >= 5) v += __shfl_xor(v, 16);
+    if (log2_lanes >= 6) v += __shfl_xor(v, 32);
+    return v;
+}
+
+}  // namespace svdp

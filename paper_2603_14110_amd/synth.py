@@ -160,7 +160,7 @@ def truncated_svd_factors(W: np.ndarray, r: int, n_sigma: Optional[int] = None):
     G = W.T @ W
     lam, U = scipy.linalg.eigh(G, subset_by_index=[d - k, d - 1])
     lam = lam[::-1]
-    U = U[:, ::-1]
+    U = np.ascontiguousarray(U[:, ::-1])
     sig = np.sqrt(np.maximum(lam, 0.0))
     Ur = U[:, :r]
     P = Ur * sig[None, :r]
@@ -253,6 +253,38 @@ def make_layer(spec: LayerSpec) -> Layer:
         "cal_pred_density": float(np.mean(S + b[None, :].astype(np.float64) > 0.0)),
     }
     return Layer(spec, W_gate_st, W_up, W_downT, P_st, Q_st, b, u, float(alpha), sig, extra)
+
+
+def load_or_make(spec: LayerSpec, cache_dir: Optional[str] = None) -> Layer:
+    """make_layer with an on-disk cache (uncompressed .npz keyed by the spec): the
+    full-size layers take tens of seconds to generate and are shared by tests and bench."""
+    import hashlib
+    import os
+
+    cache_dir = cache_dir or os.environ.get("SVDP_CACHE_DIR", "/tmp/svdp_synth_cache")
+    key = hashlib.sha1(repr(sorted(spec.__dict__.items())).encode()).hexdigest()[:16]
+    path = os.path.join(cache_dir, f"{spec.name}_{key}.npz")
+    names = ("W_gate", "W_up", "W_downT", "P", "Q", "b", "u", "sigma")
+    if os.path.exists(path):
+        try:
+            with np.load(path, allow_pickle=False) as z:
+                arrs = {k: z[k] for k in names}
+                alpha = float(z["alpha"])
+                extra = {k[6:]: float(z[k]) for k in z.files if k.startswith("extra_")}
+            return Layer(spec, arrs["W_gate"], arrs["W_up"], arrs["W_downT"], arrs["P"], arrs["Q"], arrs["b"],
+                         arrs["u"], alpha, arrs["sigma"], extra)
+        except Exception:
+            pass
+    layer = make_layer(spec)
+    try:
+        os.makedirs(cache_dir, exist_ok=True)
+        tmp = path + f".tmp{os.getpid()}.npz"
+        np.savez(tmp, alpha=np.float64(layer.alpha), **{k: getattr(layer, k) for k in names},
+                 **{"extra_" + k: np.float64(v) for k, v in layer.extra.items()})
+        os.replace(tmp, path)
+    except OSError:
+        pass
+    return layer
 
 
 def timed_tokens(layer: Layer, n: int) -> np.ndarray:

@@ -1,0 +1,94 @@
+"""CPU checks of the C-ABI boundary: the library loads, exports every symbol the
+header declares, and its host-only logic (workspace sizing, argument validation,
+status strings) behaves.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def svdp():
+    from paper_2603_14110_amd import binding, build
+
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_lib()
+    return binding
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "svdp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(svdp_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(svdp):
+    L = svdp.lib()
+    names = _declared()
+    assert set(names) == set(svdp.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings_and_version(svdp):
+    L = svdp.lib()
+    seen = {L.svdp_status_string(i).decode() for i in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert L.svdp_status_string(99) is not None
+    assert re.match(r"^\d+\.\d+$", svdp.version())
+
+
+def _layer(svdp, d=4096, D=11008, r=256, dt=1, ptr=0x1000):
+    return svdp.svdp_layer(d, D, r, dt, ptr, ptr, ptr, ptr, ptr, ptr, 0)
+
+
+def test_workspace_bytes(svdp):
+    L = svdp.lib()
+    l = _layer(svdp)
+    w1 = L.svdp_workspace_bytes(ctypes.byref(l), 1)
+    w8 = L.svdp_workspace_bytes(ctypes.byref(l), 8)
+    assert 0 < w1 < w8 < (1 << 30)
+    assert w1 % 256 == 0
+    # at least the index list, the mask words and one partial y
+    assert w1 >= 11008 * 4 + 11008 // 8 + 4096 * 4
+    assert L.svdp_workspace_bytes(ctypes.byref(l), 0) == 0
+    assert L.svdp_workspace_bytes(ctypes.byref(l), 9) == 0
+    assert L.svdp_workspace_bytes(ctypes.byref(_layer(svdp, D=11000)), 1) == 0     # D % 64
+    assert L.svdp_workspace_bytes(ctypes.byref(_layer(svdp, d=4100)), 1) == 0      # d % 8 (bf16)
+    assert L.svdp_workspace_bytes(ctypes.byref(_layer(svdp, d=4100, dt=0)), 1) > 0  # d % 4 ok for fp32
+    assert L.svdp_workspace_bytes(ctypes.byref(_layer(svdp, dt=7)), 1) == 0
+    assert L.svdp_workspace_bytes(None, 1) == 0
+
+
+def test_validation_rejects_before_any_launch(svdp):
+    """Bad arguments return an error code on the host; nothing reaches a device."""
+    L = svdp.lib()
+    l = _layer(svdp)
+    ws = 1 << 28
+    INVALID, UNSUPPORTED, WORKSPACE = 1, 2, 3
+    assert L.svdp_predict(ctypes.byref(l), None, 1, 0x1000, 0x1000, ws, None) == INVALID
+    assert L.svdp_predict(ctypes.byref(l), 0x1000, 0, 0x1000, 0x1000, ws, None) == INVALID
+    assert L.svdp_predict(ctypes.byref(l), 0x1000, 9, 0x1000, 0x1000, ws, None) == INVALID
+    assert L.svdp_predict(ctypes.byref(l), 0x1000, 1, 0x1000, None, ws, None) == WORKSPACE
+    assert L.svdp_predict(ctypes.byref(l), 0x1000, 1, 0x1000, 0x1000, 16, None) == WORKSPACE
+    assert L.svdp_predict(ctypes.byref(l), 0x1000, 1, 0x1000, 0x1010, ws, None) == WORKSPACE   # misaligned ws
+    assert L.svdp_dense_ffn(ctypes.byref(_layer(svdp, D=100)), 0x1000, 1, 0x1000, 0x1000, ws, None) == UNSUPPORTED
+    assert L.svdp_dense_ffn(ctypes.byref(_layer(svdp, ptr=0x1004)), 0x1000, 1, 0x1000, 0x1000, ws, None) == INVALID
+    assert L.svdp_sparse_ffn(ctypes.byref(l), 0x1000, 1, None, 0x1000, 0x1000, 0x1000, ws, None) == INVALID
+    assert L.svdp_ffn_step(ctypes.byref(l), 0x1000, 1, None, None, None, None, 0x1000, ws, None) == INVALID
+    bad = _layer(svdp)
+    bad.flags = 8
+    assert L.svdp_ffn_step(ctypes.byref(bad), 0x1000, 1, 0x1000, None, None, None, 0x1000, ws, None) == INVALID
+    assert L.svdp_compact(None, 1, 64, 0x1000, 0x1000, 0x1000, None) == INVALID
+    assert L.svdp_compact(0x1000, 1, 100, 0x1000, 0x1000, 0x1000, None) == UNSUPPORTED
+    assert L.svdp_stack_glue(None, 0x1000, 0x1000, 64, 0, 1e-6, 0x1000, None) == INVALID
+
+
+def test_binding_fails_loudly_without_library(svdp, monkeypatch):
+    monkeypatch.setattr(svdp, "_lib", None)
+    monkeypatch.setattr(svdp, "LIB_PATH", "/nonexistent/libsvdp.so")
+    with pytest.raises(svdp.SvdpError):
+        svdp.lib()

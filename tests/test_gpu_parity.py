@@ -1,0 +1,255 @@
+"""GPU parity: every entry point of libsvdp against the CPU oracle on the same
+seeded inputs, element by element (rules in tests/parity.py)."""
+import os
+
+import numpy as np
+import pytest
+
+import parity
+from paper_2603_14110_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(oracle):
+    import torch
+    from paper_2603_14110_amd import binding
+
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    binding.lib()          # raises if the HIP library is missing: no fallback
+    return binding, torch, oracle
+
+
+class Case:
+    """A generated layer on both sides: float32 views for the oracle, device tensors for the library."""
+
+    def __init__(self, binding, torch, spec, n_tok):
+        self.spec = spec
+        self.L = synth.load_or_make(spec) if spec.D >= 8192 else synth.make_layer(spec)
+        self.f32 = {k: self.L.f32(k) for k in ("W_gate", "W_up", "W_downT", "P", "Q", "b")}
+        self.dev = binding.DeviceLayer.from_synth(self.L)
+        self.X_st = synth.timed_tokens(self.L, n_tok)
+        self.X = synth.storage_to_f32(self.X_st, spec.dtype)
+        self.Xd = binding.to_device(self.X_st, spec.dtype)
+
+
+_cases = {}
+
+
+def get_case(env, name, n_tok=64, **over):
+    binding, torch, _ = env
+    key = (name, n_tok, tuple(sorted(over.items())))
+    if key not in _cases:
+        _cases[key] = Case(binding, torch, synth.workload(name, **over), n_tok)
+    return _cases[key]
+
+
+SMALL = [
+    ("tiny", {}),                                                             # d=256 D=1024 r=32 fp32
+    ("tiny", dict(dtype="bf16")),
+    ("tiny", dict(d=264, D=1088, r=40, dtype="bf16", seed=5)),                # ragged: nothing a power of two
+    ("tiny", dict(d=100, D=192, r=12, seed=6, k_dom=8, n_cal=128)),           # fp32, d % 64 != 0
+    ("tiny", dict(d=1024, D=2560, r=72, dtype="bf16", seed=7, k_dom=32)),     # several tiles per block
+]
+
+
+def step_check(env, c, B, t0, flags=0):
+    binding, torch, oracle = env
+    dev = c.dev.with_flags(flags) if flags else c.dev
+    x = c.Xd[t0:t0 + B]
+    D = c.spec.D
+    mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+    idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+    nnz = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    y = binding.ffn_step(dev, x, mask=mask, idx=idx, nnz=nnz)
+    torch.cuda.synchronize()
+    s_or = oracle.predict(c.f32["P"], c.f32["Q"], c.f32["b"], c.X[t0:t0 + B])
+    lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+    y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[t0:t0 + B], lst,
+                              drelu=bool(flags & 1))
+    parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype)
+    # the step without the optional outputs gives the same y, bit for bit
+    y2 = binding.ffn_step(dev, x)
+    assert torch.equal(y, y2)
+    return lst, y
+
+
+@pytest.mark.parametrize("name,over", SMALL)
+def test_predict_scores(env, name, over):
+    binding, torch, oracle = env
+    c = get_case(env, name, **over)
+    for B in (1, 2, 3, 8):
+        s = binding.predict(c.dev, c.Xd[:B]).cpu().numpy().astype(np.float64)
+        s_or = oracle.predict(c.f32["P"], c.f32["Q"], c.f32["b"], c.X[:B])
+        scale = np.abs(s_or).max(axis=1, keepdims=True)
+        assert np.all(np.abs(s - s_or) <= 2e-5 * scale), np.abs(s - s_or).max() / scale.max()
+
+
+def test_compact_bit_exact(env):
+    """Same fp32 scores on both sides -> the decision s > 0 is taken in the same precision: bit-exact."""
+    binding, torch, oracle = env
+    rng = np.random.default_rng(1)
+    for B, D in [(1, 64), (1, 1024), (3, 11008), (8, 14336), (2, 64 * 1030)]:
+        s = rng.standard_normal((B, D)).astype(np.float32) - np.float32(0.8 + 0.4 * (B > 2))
+        s[0, :8] = [0.0, -0.0, np.nan, np.inf, -np.inf, 1e-45, -1e-45, 1.0]
+        mask, idx, nnz = binding.compact(torch.from_numpy(s).cuda())
+        m_or, idx_or = oracle.compact(s.astype(np.float64))
+        n = int(nnz.item())
+        assert n == idx_or.size
+        assert np.array_equal(idx.cpu().numpy()[:n], idx_or)
+        assert np.all(idx.cpu().numpy()[n:] == -1)                    # the tail is left untouched
+        assert np.array_equal(parity.mask_bits(mask.cpu().numpy(), D), m_or.astype(bool))
+    for fill in (-1.0, 1.0):                                            # empty and full
+        s = torch.full((2, 1024), fill, device="cuda")
+        mask, idx, nnz = binding.compact(s)
+        assert nnz.item() == (1024 if fill > 0 else 0)
+        if fill > 0:
+            assert np.array_equal(idx.cpu().numpy(), np.arange(1024))
+
+
+@pytest.mark.parametrize("name,over", SMALL)
+def test_sparse_ffn_arbitrary_lists(env, name, over):
+    binding, torch, oracle = env
+    c = get_case(env, name, **over)
+    D = c.spec.D
+    rng = np.random.default_rng(2)
+    lists = [np.zeros(0, np.int32), np.array([D - 1], np.int32), np.arange(D, dtype=np.int32),
+             np.sort(rng.choice(D, D // 10, replace=False)).astype(np.int32),
+             np.sort(rng.choice(D, D // 2 + 3, replace=False)).astype(np.int32),
+             rng.permutation(D)[: D // 7].astype(np.int32)]            # unsorted lists are allowed
+    for B in (1, 2, 5, 8):
+        for lst in lists:
+            idx = torch.zeros(D, dtype=torch.int32, device="cuda")
+            idx[: lst.size] = torch.from_numpy(lst).cuda()
+            nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
+            y = binding.sparse_ffn(c.dev, c.Xd[:B], idx, nnz).cpu().numpy()
+            y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B], lst)
+            parity.check_y(y, y_ref, c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, c.X[:B], lst))
+            if lst.size == 0:
+                assert not y.any()
+
+
+@pytest.mark.parametrize("name,over", SMALL)
+def test_dense_ffn(env, name, over):
+    binding, torch, oracle = env
+    c = get_case(env, name, **over)
+    for B in (1, 4, 7):
+        y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
+        y_ref = oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B])
+        parity.check_y(y, y_ref, c.spec.dtype)
+    yd = binding.dense_ffn(c.dev.with_flags(binding.FLAG_DRELU), c.Xd[:2]).cpu().numpy()
+    parity.check_y(yd, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:2], drelu=True),
+                   c.spec.dtype)
+
+
+@pytest.mark.parametrize("name,over", SMALL)
+def test_ffn_step_all_tokens(env, name, over):
+    """Config-0 style run: every one of the 64 decode tokens, batch 1."""
+    c = get_case(env, name, **over)
+    dens = []
+    for t in range(64):
+        lst, _ = step_check(env, c, 1, t)
+        dens.append(lst.size / c.spec.D)
+    assert 0.02 < np.mean(dens) < 0.4
+
+
+@pytest.mark.parametrize("B", [2, 3, 4, 8])
+@pytest.mark.parametrize("name,over", SMALL[:3])
+def test_ffn_step_union_batches(env, name, over, B):
+    c = get_case(env, name, **over)
+    for t0 in range(0, 64 - B + 1, 8):
+        step_check(env, c, B, t0)
+
+
+def test_step_equals_separate_calls(env):
+    binding, torch, _ = env
+    c = get_case(env, "tiny")
+    for B in (1, 4):
+        x = c.Xd[8:8 + B]
+        s = binding.predict(c.dev, x)
+        mask, idx, nnz = binding.compact(s)
+        y_sep = binding.sparse_ffn(c.dev, x, idx, nnz)
+        D = c.spec.D
+        mask2 = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+        idx2 = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+        nnz2 = torch.zeros(1, dtype=torch.int32, device="cuda")
+        y = binding.ffn_step(c.dev, x, mask=mask2, idx=idx2, nnz=nnz2)
+        assert torch.equal(mask, mask2) and torch.equal(nnz, nnz2)
+        n = nnz.item()
+        assert torch.equal(idx[:n], idx2[:n])
+        assert torch.equal(y, y_sep)
+
+
+def test_flags_drelu_and_revalidate(env):
+    binding, torch, oracle = env
+    c = get_case(env, "tiny", dtype="bf16")
+    for B in (1, 4):
+        step_check(env, c, B, 3, flags=binding.FLAG_DRELU)
+        lst, y_plain = step_check(env, c, B, 3)
+        lst2, y_rev = step_check(env, c, B, 3, flags=binding.FLAG_REVALIDATE)
+        assert np.array_equal(lst, lst2)
+        # skipping rows whose gate is <= 0 removes exact zeros from the sum: same values
+        assert np.array_equal(y_plain.cpu().numpy(), y_rev.cpu().numpy())
+
+
+def test_deterministic(env):
+    """Fixed summation order (App. C): bitwise identical output run to run."""
+    binding, torch, _ = env
+    c = get_case(env, "tiny", d=1024, D=2560, r=72, dtype="bf16", seed=7, k_dom=32)
+    for B in (1, 8):
+        ref = binding.ffn_step(c.dev, c.Xd[:B]).clone()
+        refd = binding.dense_ffn(c.dev, c.Xd[:B]).clone()
+        for _ in range(20):
+            assert torch.equal(binding.ffn_step(c.dev, c.Xd[:B]), ref)
+            assert torch.equal(binding.dense_ffn(c.dev, c.Xd[:B]), refd)
+
+
+def test_degenerate_masks(env):
+    """Nothing active (very negative bias) and everything active (very positive bias)."""
+    binding, torch, oracle = env
+    c = get_case(env, "tiny")
+    t = c.dev.tensors
+    for fill, expect in ((-1e6, 0), (1e6, c.spec.D)):
+        b = torch.full_like(t["b"], fill)
+        dev = binding.DeviceLayer(t["P"], t["Q"], b, t["W_gate"], t["W_up"], t["W_downT"])
+        nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+        y = binding.ffn_step(dev, c.Xd[:2], nnz=nnz).cpu().numpy()
+        assert nnz.item() == expect
+        if expect == 0:
+            assert not y.any()
+        else:
+            parity.check_y(y, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:2]), "f32")
+
+
+def test_stack_glue(env):
+    binding, torch, oracle = env
+    rng = np.random.default_rng(3)
+    for d, dt in [(256, "f32"), (4096, "bf16"), (264, "bf16")]:
+        x_st = synth.to_storage(rng.standard_normal(d), dt)
+        y = rng.standard_normal(d).astype(np.float32)
+        sh = rng.standard_normal(d).astype(np.float32)
+        out = binding.stack_glue(binding.to_device(x_st, dt), torch.from_numpy(y).cuda(), torch.from_numpy(sh).cuda())
+        ref = oracle.stack_glue(synth.storage_to_f32(x_st, dt), y, sh)
+        got = out.float().cpu().numpy().astype(np.float64)
+        tol = 2e-6 if dt == "f32" else 2.0 ** -8
+        assert np.all(np.abs(got - ref) <= tol * np.maximum(np.abs(ref), 1.0))
+
+
+# ---- full-size layers, in the launch configuration the benchmark times ----------------
+
+
+FULL = [("7b", {}, 1), ("7b", dict(r=128), 1), ("7b", dict(r=512), 1), ("13b", {}, 1),
+        ("mistral", {}, 1), ("mistral", {}, 2), ("mistral", {}, 4), ("mistral", {}, 8)]
+
+
+@pytest.mark.parametrize("name,over,B", FULL)
+def test_full_size_sampled_tokens(env, name, over, B):
+    """Full shapes; a sample of decode steps checked completely (mask, list, y) against the
+    oracle, plus the dense baseline on one batch."""
+    binding, torch, oracle = env
+    c = get_case(env, name, n_tok=64, **over)
+    for t0 in (0, 8, 16, 24):
+        step_check(env, c, B, t0)
+    y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
+    parity.check_y(y, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B]), c.spec.dtype)
