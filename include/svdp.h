@@ -27,7 +27,7 @@
  *
  * Shape limits (else SVDP_ERR_UNSUPPORTED): D % 64 == 0, and with
  * e = 4 (fp32) or 8 (bf16) elements per 16 bytes: d % e == 0, r % e == 0,
- * r <= 1024 (fp32) or 2048 (bf16), d <= 16384.  Every matrix pointer must be 16-byte aligned.
+ * r <= 2048, d <= 16384.  Every matrix pointer must be 16-byte aligned.
  */
 #ifndef SVDP_H
 #define SVDP_H

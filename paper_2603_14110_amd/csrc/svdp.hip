@@ -10,7 +10,7 @@ namespace {
 
 using namespace svdp;
 
-constexpr int XP_MAX_BLOCKS = 64;     // stage-1 row slabs of P
+constexpr int XP_MAX_BLOCKS = 128;    // stage-1 row slabs of P (d <= 16384)
 constexpr int ROWS_GRID = 512;        // k_rows blocks (chunks of the row list)
 constexpr size_t ALIGN = 256;
 
@@ -26,7 +26,7 @@ svdp_status check_shape(int d, int D, int r, int dt)
     if (d <= 0 || D <= 0 || r <= 0) return SVDP_ERR_INVALID_ARG;
     const int e = vec_of(dt);
     if (D % 64 != 0 || d % e != 0 || r % e != 0) return SVDP_ERR_UNSUPPORTED;
-    if (r / e > XP_THREADS || r > 2048 || d > 16384) return SVDP_ERR_UNSUPPORTED;
+    if (r > 2048 || d > 16384) return SVDP_ERR_UNSUPPORTED;
     return SVDP_OK;
 }
 
@@ -109,16 +109,27 @@ svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, i
 {
     constexpr int VEC = Elem<W>::VEC;
     const int d = L->d, r = L->r;
-    int nt = d / 64;
-    nt = nt < 1 ? 1 : (nt > XP_MAX_BLOCKS ? XP_MAX_BLOCKS : nt);
-    const int rows = (d + nt - 1) / nt;
-    nt = (d + rows - 1) / rows;
-    const size_t lds = ((size_t)NB * rows + (size_t)XP_THREADS * VEC * NB) * 4;
+    const int nt = (d + XP_ROWS - 1) / XP_ROWS;           // <= XP_MAX_BLOCKS since d <= 16384
+    const int ncs = (r + XP_COLS - 1) / XP_COLS;
+    const size_t lds = ((size_t)NB * XP_ROWS + (size_t)(XP_THREADS / (XP_COLS / VEC)) * NB * XP_COLS) * 4;
     static int granted = 64 * 1024;
     if (allow_lds(k_xP<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_xP<W, NB>), dim3(nt), dim3(XP_THREADS), lds, st, static_cast<const W *>(L->P),
-                       static_cast<const W *>(x), B, d, r, rows, tpart);
+    hipLaunchKernelGGL((k_xP<W, NB>), dim3(nt, ncs), dim3(XP_THREADS), lds, st, static_cast<const W *>(L->P),
+                       static_cast<const W *>(x), B, d, r, tpart);
     *nt_out = nt;
+    return hip_status(hipSuccess);
+}
+
+template <typename W, int NB, int LPR_LOG2>
+svdp_status launch_scores_lpr(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
+                              uint64_t *mask_out, hipStream_t st)
+{
+    const size_t tsp = (size_t)NB * L->r > (size_t)SC_THREADS * 4 ? (size_t)NB * L->r : (size_t)SC_THREADS * 4;
+    const size_t lds = ((size_t)NB * L->r + (size_t)NB * SC_SLAB + tsp) * 4;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_scores<W, NB, LPR_LOG2>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_scores<W, NB, LPR_LOG2>), dim3(L->D / SC_SLAB), dim3(SC_THREADS), lds, st,
+                       static_cast<const W *>(L->Q), L->b, tpart, nt, B, L->D, L->r, s_out, mask_out);
     return hip_status(hipSuccess);
 }
 
@@ -126,36 +137,33 @@ template <typename W, int NB>
 svdp_status launch_scores(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
                           uint64_t *mask_out, hipStream_t st)
 {
-    constexpr int VEC = Elem<W>::VEC;
-    const int cg = L->r / VEC;
-    int lpr_log2 = 0;
-    while ((1 << lpr_log2) < cg && lpr_log2 < 6) ++lpr_log2;
-    const size_t lds = ((size_t)NB * L->r + (size_t)NB * SC_SLAB) * 4;
-    static int granted = 64 * 1024;
-    if (allow_lds(k_scores<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_scores<W, NB>), dim3(L->D / SC_SLAB), dim3(SC_THREADS), lds, st,
-                       static_cast<const W *>(L->Q), L->b, tpart, nt, B, L->D, L->r, lpr_log2, s_out, mask_out);
-    return hip_status(hipSuccess);
+    const int cg = L->r / Elem<W>::VEC;       // 16-byte column groups per row of Q
+    if (cg <= 8) return launch_scores_lpr<W, NB, 3>(L, tpart, nt, B, s_out, mask_out, st);
+    if (cg <= 16) return launch_scores_lpr<W, NB, 4>(L, tpart, nt, B, s_out, mask_out, st);
+    if (cg <= 32) return launch_scores_lpr<W, NB, 5>(L, tpart, nt, B, s_out, mask_out, st);
+    return launch_scores_lpr<W, NB, 6>(L, tpart, nt, B, s_out, mask_out, st);
 }
 
-template <typename W, int NB, bool DENSE>
-svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const int32_t *idx, const int32_t *nnz,
-                        float *ypart, float *y, hipStream_t st)
+template <typename W, int NB, int MODE>
+svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
+                        const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, float *y,
+                        hipStream_t st)
 {
     const int d = L->d, D = L->D;
-    const int max_chunk = (D + ROWS_GRID - 1) / ROWS_GRID;
-    const size_t lds = ((size_t)NB * d + (size_t)NB * max_chunk) * 4;
+    const int max_chunk = ((D + ROWS_GRID - 1) / ROWS_GRID + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
+    const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
     static int granted = 64 * 1024;
-    if (allow_lds(k_rows<W, NB, DENSE>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_rows<W, NB, DENSE>), dim3(ROWS_GRID), dim3(ROWS_THREADS), lds, st,
+    if (allow_lds(k_rows<W, NB, MODE>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_rows<W, NB, MODE>), dim3(ROWS_GRID), dim3(ROWS_THREADS), lds, st,
                        static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
-                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, idx, nnz,
-                       max_chunk, L->flags, ypart);
+                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, mask, idx_in, nnz_in,
+                       idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart);
     svdp_status s = hip_status(hipSuccess);
     if (s != SVDP_OK) return s;
-    const int threads = B * (d / 4);
-    hipLaunchKernelGGL(k_reduce_y, dim3((threads + 255) / 256), dim3(256), 0, st, ypart,
-                       DENSE ? nullptr : nnz, D, D, ROWS_GRID, NB, B, d, y);
+    const int vpt = d / 4;
+    const int blocks = B * ((vpt + RED_COLS - 1) / RED_COLS);
+    hipLaunchKernelGGL(k_reduce_y, dim3(blocks), dim3(RED_COLS * RED_SEGS), 0, st, w.ypart,
+                       MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, ROWS_GRID, NB, B, d, y);
     return hip_status(hipSuccess);
 }
 
@@ -202,13 +210,9 @@ svdp_status run_step(const svdp_layer *L, const void *x, int B, float *y, uint64
                      int32_t *nnz_out, const Workspace &w, hipStream_t st)
 {
     uint64_t *mask = mask_out ? mask_out : w.mask;
-    int32_t *idx = idx_out ? idx_out : w.idx;
-    int32_t *nnz = nnz_out ? nnz_out : w.nnz;
     svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st);
     if (e != SVDP_OK) return e;
-    e = launch_compact(mask, L->D, idx, nnz, st);
-    if (e != SVDP_OK) return e;
-    return launch_rows<W, NB, false>(L, x, B, idx, nnz, w.ypart, y, st);
+    return launch_rows<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, idx_out, nnz_out, w, y, st);
 }
 
 svdp_status dispatch_predict(const svdp_layer *L, const void *x, int B, float *s, const Workspace &w, hipStream_t st)
@@ -218,11 +222,11 @@ svdp_status dispatch_predict(const svdp_layer *L, const void *x, int B, float *s
 svdp_status dispatch_sparse(const svdp_layer *L, const void *x, int B, const int32_t *idx, const int32_t *nnz,
                             float *y, const Workspace &w, hipStream_t st)
 {
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, false>(L, x, B, idx, nnz, w.ypart, y, st)));
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, ROWS_LIST>(L, x, B, nullptr, idx, nnz, nullptr, nullptr, w, y, st)));
 }
 svdp_status dispatch_dense(const svdp_layer *L, const void *x, int B, float *y, const Workspace &w, hipStream_t st)
 {
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, true>(L, x, B, nullptr, nullptr, w.ypart, y, st)));
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, ROWS_DENSE>(L, x, B, nullptr, nullptr, nullptr, nullptr, nullptr, w, y, st)));
 }
 svdp_status dispatch_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out,
                           int32_t *idx_out, int32_t *nnz_out, const Workspace &w, hipStream_t st)
@@ -334,5 +338,16 @@ const char *svdp_status_string(svdp_status st)
 }
 
 const char *svdp_version(void) { return "0.1"; }
+
+#ifdef SVDP_TRACE
+// Debug builds only: copy the phase time stamps to the host (synchronises).
+int svdp_debug_read_trace(unsigned long long *host, size_t count)
+{
+    const size_t total = sizeof(svdp::g_trace) / sizeof(svdp::g_trace[0]);
+    if (count > total) count = total;
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(svdp::g_trace), count * sizeof(unsigned long long), 0,
+                                    hipMemcpyDeviceToHost);
+}
+#endif
 
 }  // extern "C"

@@ -7,6 +7,32 @@
 
 namespace svdp {
 
+// Optional phase time stamps (debug builds with -DSVDP_TRACE only): lane 0 of every
+// block records the 100 MHz real-time counter at numbered points of a kernel.
+#ifdef SVDP_TRACE
+constexpr int TRACE_SLOTS = 8;
+constexpr int TRACE_BLOCKS = 512;
+constexpr int TRACE_KERNELS = 4;
+__device__ unsigned long long g_trace[TRACE_KERNELS * TRACE_BLOCKS * TRACE_SLOTS];
+#define SVDP_STAMP(kernel_id, slot)                                                                   \
+    do {                                                                                              \
+        if (threadIdx.x == 0 && blockIdx.x < TRACE_BLOCKS && blockIdx.y == 0)                         \
+            g_trace[((kernel_id)*TRACE_BLOCKS + blockIdx.x) * TRACE_SLOTS + (slot)] = wall_clock64(); \
+    } while (0)
+#define SVDP_STAMP_CLK(kernel_id, slot)                                                               \
+    do {                                                                                              \
+        if (threadIdx.x == 0 && blockIdx.x < TRACE_BLOCKS && blockIdx.y == 0)                         \
+            g_trace[((kernel_id)*TRACE_BLOCKS + blockIdx.x) * TRACE_SLOTS + (slot)] = clock64();      \
+    } while (0)
+#else
+#define SVDP_STAMP_CLK(kernel_id, slot) \
+    do {                                \
+    } while (0)
+#define SVDP_STAMP(kernel_id, slot) \
+    do {                            \
+    } while (0)
+#endif
+
 // bfloat16 storage element (bit pattern only; all arithmetic is fp32, the
 // "full precision registers, half precision memory" policy of the paper's App. C).
 struct bf16 {
@@ -58,6 +84,46 @@ __device__ __forceinline__ void load_vec(const bf16 *p, float (&v)[8])
     v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
 }
 
+// Raw 16-byte load (issued early, widened later) and its widening to fp32.
+template <typename W>
+__device__ __forceinline__ uint4 load_raw(const W *p)
+{
+    return *reinterpret_cast<const uint4 *>(p);
+}
+__device__ __forceinline__ void widen(const uint4 &q, float (&v)[4], const float *)
+{
+    v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y);
+    v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
+}
+__device__ __forceinline__ void widen(const uint4 &q, float (&v)[8], const bf16 *)
+{
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+    v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+}
+
+// Dot product of two raw 16-byte vectors of storage elements, accumulated in fp32.
+// bf16: four packed two-element dot instructions (bf16 x bf16 products are exact in
+// fp32; the sum is rounded to fp32); fp32: four fused multiply-adds.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot_raw(const uint4 &w, const uint4 &x, float acc, const float *)
+{
+    acc = fmaf(__uint_as_float(w.x), __uint_as_float(x.x), acc);
+    acc = fmaf(__uint_as_float(w.y), __uint_as_float(x.y), acc);
+    acc = fmaf(__uint_as_float(w.z), __uint_as_float(x.z), acc);
+    acc = fmaf(__uint_as_float(w.w), __uint_as_float(x.w), acc);
+    return acc;
+}
+__device__ __forceinline__ float dot_raw(const uint4 &w, const uint4 &x, float acc, const bf16 *)
+{
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x), __builtin_bit_cast(bf16x2_t, x.x), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y), __builtin_bit_cast(bf16x2_t, x.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z), __builtin_bit_cast(bf16x2_t, x.z), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w), __builtin_bit_cast(bf16x2_t, x.w), acc, false);
+    return acc;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v)
 {
@@ -80,16 +146,36 @@ __device__ __forceinline__ float wave_sum(float v)
     return (a + b) + (c + d);
 }
 
+// Inclusive prefix sum of one int per lane over the wave (lane order), on DPP row
+// shifts and row broadcasts; lane 63 ends up with the wave total.
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ int dpp_take(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, BANK_MASK, true);
+}
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    int s = v + dpp_take<0x111, 0xf, 0xf>(v);      // row_shr:1
+    s += dpp_take<0x112, 0xf, 0xf>(v);             // row_shr:2
+    s += dpp_take<0x113, 0xf, 0xf>(v);             // row_shr:3
+    s += dpp_take<0x114, 0xf, 0xe>(s);             // row_shr:4, lanes 4..15 of each row
+    s += dpp_take<0x118, 0xf, 0xc>(s);             // row_shr:8, lanes 8..15 of each row
+    s += dpp_take<0x142, 0xa, 0xf>(s);             // row_bcast:15 into rows 1 and 3
+    s += dpp_take<0x143, 0xc, 0xf>(s);             // row_bcast:31 into rows 2 and 3
+    return s;
+}
+
 // Sum over aligned groups of 2^LOG2 consecutive lanes; every lane of a group
 // gets the group's sum.  Butterfly order, fixed.
-__device__ __forceinline__ float group_sum(float v, int log2_lanes)
+template <int LOG2>
+__device__ __forceinline__ float group_sum(float v)
 {
-    if (log2_lanes >= 1) v += dpp_move<0xB1>(v);
-    if (log2_lanes >= 2) v += dpp_move<0x4E>(v);
-    if (log2_lanes >= 3) v += dpp_move<0x141>(v);
-    if (log2_lanes >= 4) v += dpp_move<0x140>(v);
-    if (log2_lanes >= 5) v += __shfl_xor(v, 16);
-    if (log2_lanes >= 6) v += __shfl_xor(v, 32);
+    if (LOG2 >= 1) v += dpp_move<0xB1>(v);
+    if (LOG2 >= 2) v += dpp_move<0x4E>(v);
+    if (LOG2 >= 3) v += dpp_move<0x141>(v);
+    if (LOG2 >= 4) v += dpp_move<0x140>(v);
+    if (LOG2 >= 5) v += __shfl_xor(v, 16);
+    if (LOG2 >= 6) v += __shfl_xor(v, 32);
     return v;
 }
 

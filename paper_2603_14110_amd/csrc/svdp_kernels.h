@@ -10,131 +10,214 @@
 namespace svdp {
 
 constexpr int XP_THREADS = 256;      // k_xP block
-constexpr int SC_THREADS = 256;      // k_scores block
+constexpr int XP_ROWS = 256;         // rows of P per k_xP block
+constexpr int XP_COLS = 32;          // columns of P per k_xP block
+constexpr int SC_THREADS = 1024;     // k_scores block
 constexpr int SC_SLAB = 64;          // neurons per k_scores block = one mask word
 constexpr int ROWS_THREADS = 512;    // k_rows block
+constexpr int ROWS_WAVES = ROWS_THREADS / 64;
+constexpr int ROWS_UB = 4;           // k_rows: rows of W_downT fetched together (chunk padded to this)
 constexpr int SCAN_THREADS = 1024;   // k_compact_scan block
+constexpr int RED_COLS = 4;          // k_reduce_y: float4 columns per block
+constexpr int RED_SEGS = 256;        // k_reduce_y: segments of the partial list per block (a power of 4)
 
 // ---------------------------------------------------------------------------
-// Predictor stage 1: partial t = x P over a slab of rows of P   (Sec. 4.1 eq. 2:
-// the inner factor B x of A B x + b, with P = B^T).
-// Block g owns rows [g*rows_per_wg, (g+1)*rows_per_wg) of P [d][r] and writes
-// tpart[g][b][0..r).  A thread owns one 16-byte column group and every
-// nsub-th row of the slab; the nsub row-partials are then added through LDS.
-// Dynamic LDS: NB*rows_per_wg + XP_THREADS*VEC*NB floats.
+// Predictor stage 1: partial t = x P over a tile of P   (Sec. 4.1 eq. 2: the
+// inner factor B x of A B x + b, with P = B^T).
+// Block (i, j) owns rows [i*XP_ROWS, +XP_ROWS) and columns [j*XP_COLS, +XP_COLS)
+// of P [d][r] and writes tpart[i][b][its columns].  A thread owns one 16-byte
+// column group and every NSUB-th row of the tile; its loads of P are issued
+// before x is staged, and the NSUB row-partials are added through LDS in order.
+// Dynamic LDS: NB*XP_ROWS + NSUB*NB*XP_COLS floats.
 // ---------------------------------------------------------------------------
 template <typename W, int NB>
 __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, const W *__restrict__ x,
-                                                   int B, int d, int r, int rows_per_wg,
-                                                   float *__restrict__ tpart)
+                                                   int B, int d, int r, float *__restrict__ tpart)
 {
     constexpr int VEC = Elem<W>::VEC;
+    constexpr int CG = XP_COLS / VEC;          // column groups per tile
+    constexpr int NSUB = XP_THREADS / CG;      // row phases
+    constexpr int RPT = XP_ROWS / NSUB;        // rows per thread
     extern __shared__ float smem[];
-    float *xs = smem;                         // [NB][rows_per_wg]
-    float *red = smem + NB * rows_per_wg;     // [nsub][NB][r]
+    float *xs = smem;                          // [NB][XP_ROWS]
+    float *red = smem + NB * XP_ROWS;          // [NSUB][NB][XP_COLS]
     const int tid = threadIdx.x;
-    const int cg = r / VEC;                   // column groups, <= XP_THREADS
-    const int nsub = XP_THREADS / cg;
-    const int j0 = blockIdx.x * rows_per_wg;
-    const int j1 = min(d, j0 + rows_per_wg);
+    const int j0 = blockIdx.x * XP_ROWS;
+    const int c0 = blockIdx.y * XP_COLS;
+    const int cgi = tid % CG, sub = tid / CG;
+    const int col = c0 + cgi * VEC;
+    const bool colok = col < r;
+    SVDP_STAMP(0, 0);
 
-    for (int i = tid; i < NB * rows_per_wg; i += XP_THREADS) {
-        const int b = i / rows_per_wg, j = j0 + i % rows_per_wg;
-        xs[i] = (b < B && j < j1) ? to_f32(x[(size_t)b * d + j]) : 0.f;
+    uint4 raw[RPT];
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        const int j = j0 + sub + k * NSUB;
+        if (colok && j < d) raw[k] = load_raw(P + (size_t)j * r + col);
+    }
+    for (int i = tid; i < NB * XP_ROWS; i += XP_THREADS) {
+        const int b = i / XP_ROWS, j = j0 + i % XP_ROWS;
+        xs[i] = (b < B && j < d) ? to_f32(x[(size_t)b * d + j]) : 0.f;
     }
     __syncthreads();
 
-    const int cgi = tid % cg, sub = tid / cg;
     float acc[NB][VEC];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[b][e] = 0.f;
-
-    if (sub < nsub) {
-        const W *col = P + (size_t)cgi * VEC;
-#pragma unroll 4
-        for (int j = j0 + sub; j < j1; j += nsub) {
+#pragma unroll
+    for (int k = 0; k < RPT; ++k) {
+        const int jj = sub + k * NSUB;
+        if (colok && j0 + jj < d) {
             float w[VEC];
-            load_vec(col + (size_t)j * r, w);
+            widen(raw[k], w, (const W *)nullptr);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const float xv = xs[b * rows_per_wg + (j - j0)];
+                const float xv = xs[b * XP_ROWS + jj];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) acc[b][e] = fmaf(xv, w[e], acc[b][e]);
             }
         }
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) red[(sub * NB + b) * r + cgi * VEC + e] = acc[b][e];
     }
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) red[(sub * NB + b) * XP_COLS + cgi * VEC + e] = acc[b][e];
     __syncthreads();
-    for (int c = tid; c < NB * r; c += XP_THREADS) {
-        const int b = c / r, k = c % r;
+    // two-level sum of the NSUB row phases: PARTS threads per output column first
+    constexpr int PARTS = XP_THREADS / XP_COLS;            // 8
+    constexpr int PER = NSUB / PARTS;
+    for (int b = 0; b < NB; ++b) {
+        const int k = tid % XP_COLS, part = tid / XP_COLS;
         float s = 0.f;
-        for (int q = 0; q < nsub; ++q) s += red[(q * NB + b) * r + k];
-        tpart[((size_t)blockIdx.x * NB + b) * r + k] = s;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) s += red[((part * PER + q) * NB + b) * XP_COLS + k];
+        __syncthreads();
+        red[(part * NB + b) * XP_COLS + k] = s;
+        __syncthreads();
+        if (part == 0 && c0 + k < r) {
+            float t = 0.f;
+#pragma unroll
+            for (int q = 0; q < PARTS; ++q) t += red[(q * NB + b) * XP_COLS + k];
+            tpart[((size_t)blockIdx.x * NB + b) * r + c0 + k] = t;
+        }
+        __syncthreads();
     }
+    SVDP_STAMP(0, 1);
 }
 
 // ---------------------------------------------------------------------------
 // Predictor stage 2 + step function: s_i = t . Q[i,:] + b_i for one slab of 64
 // neurons, then (optionally) the 64-bit mask word of the slab:
 // bit j = OR over tokens of [s > 0]   (eq. 2's H; the union over the batch).
-// t is first assembled from the nt stage-1 partials (fixed order) into LDS.
-// A group of 2^lpr_log2 lanes owns one row of Q at a time.
-// Dynamic LDS: NB*r + NB*64 floats.
+// A group of LPR = 2^LPR_LOG2 lanes owns every NGRP-th row of the slab; a lane
+// owns the column groups lig, lig+LPR, ... of its rows.  The rows' first column
+// groups are requested first; then t is assembled from the nt stage-1 partials
+// (threads split the partial list, all loads in flight, fixed combination
+// order through LDS), so the memory latencies overlap.
+// Dynamic LDS: NB*r + NB*64 + max(SC_THREADS*4, NB*r) floats.
 // ---------------------------------------------------------------------------
-template <typename W, int NB>
+template <typename W, int NB, int LPR_LOG2>
 __global__ __launch_bounds__(SC_THREADS) void k_scores(const W *__restrict__ Q,
                                                        const float *__restrict__ bias,
                                                        const float *__restrict__ tpart, int nt, int B,
-                                                       int D, int r, int lpr_log2,
-                                                       float *__restrict__ s_out,
+                                                       int D, int r, float *__restrict__ s_out,
                                                        uint64_t *__restrict__ mask_out)
 {
     constexpr int VEC = Elem<W>::VEC;
+    constexpr int LPR = 1 << LPR_LOG2;              // lanes per row: 8, 16, 32 or 64
+    constexpr int NGRP = SC_THREADS / LPR;          // lane groups per block
+    constexpr int RPG = (SC_SLAB + NGRP - 1) / NGRP;   // rows per lane group (groups beyond the slab idle)
     extern __shared__ float smem[];
-    float *ts = smem;              // [NB][r]
-    float *sc = smem + NB * r;     // [NB][64]
+    float *ts = smem;                  // [NB][r]
+    float *sc = ts + NB * r;           // [NB][64]
+    float *tsp = sc + NB * SC_SLAB;    // [npg][NB*r] partial sums of t
     const int tid = threadIdx.x;
     const int i0 = blockIdx.x * SC_SLAB;
-
-    for (int c = tid; c < NB * r; c += SC_THREADS) {
-        float s = 0.f;
-        for (int g = 0; g < nt; ++g) s += tpart[(size_t)g * NB * r + c];
-        ts[c] = s;
-    }
-    __syncthreads();
-
-    const int lpr = 1 << lpr_log2;
-    const int lig = tid & (lpr - 1);
-    const int grp = tid >> lpr_log2;
-    const int ngrp = SC_THREADS >> lpr_log2;
+    const int lig = tid & (LPR - 1);
+    const int grp = tid >> LPR_LOG2;
     const int cg = r / VEC;
-    for (int n = grp; n < SC_SLAB; n += ngrp) {
-        const W *row = Q + (size_t)(i0 + n) * r;
-        float acc[NB];
+    SVDP_STAMP(1, 0);
+    const float my_bias = tid < SC_SLAB ? bias[i0 + tid] : 0.f;     // added after the row sums
+
+    // first column group of each of this group's rows
+    uint4 raw[RPG];
+    const bool has_rows = NGRP <= SC_SLAB || grp < SC_SLAB;
+    const W *qrow = Q + (size_t)(i0 + (has_rows ? grp : 0)) * r + (lig < cg ? lig : 0) * VEC;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[b] = 0.f;
-        for (int v = lig; v < cg; v += lpr) {
-            float w[VEC];
-            load_vec(row + v * VEC, w);
+    for (int k = 0; k < RPG; ++k) raw[k] = load_raw(qrow + (size_t)k * NGRP * r);
+
+    {   // t = sum of the stage-1 partials
+        const int ncq = NB * r / 4;                        // float4 columns of t
+        const int npg = max(1, SC_THREADS / ncq);          // threads per column
+        const float4 *tp4 = reinterpret_cast<const float4 *>(tpart);
+        float4 *tsp4 = reinterpret_cast<float4 *>(tsp);
+        for (int it = tid; it < ncq * npg; it += SC_THREADS) {
+            const int cq = it % ncq, pg = it / ncq;
+            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+            for (int g = pg; g < nt; g += npg) {
+                const float4 p = tp4[(size_t)g * ncq + cq];
+                s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+            }
+            tsp4[pg * ncq + cq] = s;
+        }
+        __syncthreads();
+        float4 *ts4 = reinterpret_cast<float4 *>(ts);
+        for (int c = tid; c < ncq; c += SC_THREADS) {
+            float4 s = tsp4[c];
+            for (int pg = 1; pg < npg; ++pg) {
+                const float4 p = tsp4[pg * ncq + c];
+                s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+            }
+            ts4[c] = s;
+        }
+        __syncthreads();
+    }
+    SVDP_STAMP(1, 1);
+
+    float acc[RPG][NB];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const float *tb = ts + b * r + v * VEC;
+    for (int k = 0; k < RPG; ++k)
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[b] = fmaf(tb[e], w[e], acc[b]);
+        for (int b = 0; b < NB; ++b) acc[k][b] = 0.f;
+    if (lig < cg) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float tv[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) tv[e] = ts[b * r + lig * VEC + e];
+#pragma unroll
+            for (int k = 0; k < RPG; ++k) {
+                float w[VEC];
+                widen(raw[k], w, (const W *)nullptr);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[k][b] = fmaf(tv[e], w[e], acc[k][b]);
             }
         }
+    }
+    for (int v = lig + LPR; v < cg && has_rows; v += LPR) {          // only when r/VEC > 64
+        for (int k = 0; k < RPG; ++k) {
+            float w[VEC];
+            load_vec(Q + (size_t)(i0 + grp + k * NGRP) * r + v * VEC, w);
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[b] = group_sum(acc[b], lpr_log2);
-        if (lig == 0) {
-            const float bi = bias[i0 + n];
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int b = 0; b < NB; ++b) sc[b * SC_SLAB + n] = acc[b] + bi;
+                for (int e = 0; e < VEC; ++e) acc[k][b] = fmaf(ts[b * r + v * VEC + e], w[e], acc[k][b]);
         }
+    }
+#pragma unroll
+    for (int k = 0; k < RPG; ++k)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const float t = group_sum<LPR_LOG2>(acc[k][b]);
+            if (lig == 0 && has_rows) sc[b * SC_SLAB + grp + k * NGRP] = t;
+        }
+    __syncthreads();
+    if (tid < SC_SLAB) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) sc[b * SC_SLAB + tid] += my_bias;
     }
     __syncthreads();
 
@@ -150,6 +233,7 @@ __global__ __launch_bounds__(SC_THREADS) void k_scores(const W *__restrict__ Q,
         const uint64_t m = __ballot(on);
         if (tid == 0) mask_out[blockIdx.x] = m;
     }
+    SVDP_STAMP(1, 2);
 }
 
 // ---------------------------------------------------------------------------
@@ -186,12 +270,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_compact_scan(const uint64_t *_
         const int k = base + tid;
         const uint64_t w = k < nwords ? mask[k] : 0ull;
         const int c = __popcll(w);
-        int inc = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(inc, o);
-            if (lane >= o) inc += t;
-        }
+        const int inc = wave_inclusive_scan(c);
         if (lane == 63) wsum[wave] = inc;
         __syncthreads();
         int wbase = 0, tot = 0;
@@ -218,67 +297,184 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_compact_scan(const uint64_t *_
 
 // ---------------------------------------------------------------------------
 // Gate, up and down over a list of rows (Alg. 3's SparseGate / SparseUpAndMul /
-// SparseDown in one launch; with DENSE the list is 0..D-1, i.e. eq. 1).
+// SparseDown in one launch).  Where the list comes from:
+//   ROWS_DENSE : all D rows (eq. 1, the dense baseline)
+//   ROWS_LIST  : idx_in[0 .. *nnz_in)           (svdp_sparse_ffn)
+//   ROWS_MASK  : the set bits of mask[0 .. D/64) (svdp_ffn_step): every block
+//                scans the popcounts of the mask words itself (Alg. 4's
+//                nonzero, without a separate launch) and extracts its own
+//                part of the ascending list; when idx_out / nnz_out are given
+//                each block also writes its part of the list there.
 // The list of n rows is cut into gridDim.x contiguous chunks; block g handles
 // chunk g:
 //   phase A: one wave per row: g = W_gate[i].x, u = W_up[i].x (wave reduction),
 //            h = ReLU(g)*u to LDS;
 //   phase B: every thread owns 16-byte column groups of the output and adds
 //            h * W_downT[i][cols] over the chunk in list order -> ypart[g].
-// Blocks with an empty chunk write nothing; k_reduce_y knows how many wrote.
-// Dynamic LDS: NB*d + NB*max_chunk floats.
+//            The first rows of W_downT are requested before phase A starts.
+// Blocks with an empty chunk write nothing; block 0 records n for k_reduce_y.
+// max_chunk (the LDS row capacity) is a multiple of ROWS_UB.
+// Dynamic LDS: NB*d storage elements (x as stored), NB*max_chunk floats, max_chunk ints.
 // ---------------------------------------------------------------------------
+enum RowsMode { ROWS_DENSE = 0, ROWS_LIST = 1, ROWS_MASK = 2 };
+
 __device__ __forceinline__ int chunk_of(int n, int G) { return (n + G - 1) / G; }
 
-template <typename W, int NB, bool DENSE>
-__global__ __launch_bounds__(ROWS_THREADS) void k_rows(const W *__restrict__ Wg, const W *__restrict__ Wu,
-                                                       const W *__restrict__ WdT, const W *__restrict__ x,
-                                                       int B, int d, int D,
-                                                       const int32_t *__restrict__ idx,
-                                                       const int32_t *__restrict__ nnz_p, int max_chunk,
-                                                       uint32_t flags, float *__restrict__ ypart)
+template <typename W, int NB, int MODE>
+__global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4))) void k_rows(
+    const W *__restrict__ Wg, const W *__restrict__ Wu, const W *__restrict__ WdT, const W *__restrict__ x, int B,
+    int d, int D, const uint64_t *__restrict__ mask, const int32_t *__restrict__ idx_in,
+    const int32_t *__restrict__ nnz_in, int32_t *__restrict__ idx_out, int32_t *__restrict__ nnz_out,
+    int32_t *__restrict__ n_used, int max_chunk, uint32_t flags, float *__restrict__ ypart)
 {
     constexpr int VEC = Elem<W>::VEC;
-    extern __shared__ float smem[];
-    float *xs = smem;              // [NB][d]
-    float *hs = smem + NB * d;     // [NB][max_chunk]
+    constexpr int UA = NB <= 2 ? 8 : 4;     // 16-byte loads in flight per matrix in phase A
+    constexpr int UB = ROWS_UB;             // rows of W_downT per group in phase B
+    extern __shared__ uint4 smem16[];
+    const int nvec = d / VEC;
+    uint4 *xraw = smem16;                                        // [NB][nvec] x in storage form
+    float *hs = reinterpret_cast<float *>(xraw + NB * nvec);     // [NB][max_chunk]
+    int *lidx = reinterpret_cast<int *>(hs + NB * max_chunk);    // [max_chunk]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int n = DENSE ? D : *nnz_p;
-    n = max(0, min(n, D));
-    const int chunk = chunk_of(n, gridDim.x);
-    const int lo = blockIdx.x * chunk;
+    const int G = gridDim.x;
+    SVDP_STAMP(2, 0);
+    SVDP_STAMP_CLK(2, 6);
+
+    // ---- stage x as stored (no conversion); rows of a batch beyond B are zero ----
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+        for (int v = tid; v < nvec; v += ROWS_THREADS)
+            xraw[b * nvec + v] = b < B ? load_raw(x + (size_t)b * d + (size_t)v * VEC) : make_uint4(0u, 0u, 0u, 0u);
+
+    // ---- the list: n, this block's chunk [lo, hi) ----
+    // ROWS_MASK: every wave scans the popcounts of all mask words by itself (lane l owns
+    // the wpl consecutive words starting at l*wpl), so no block-wide step is needed.
+    int n, lane_first = 0, wpl = 0;
+    if (MODE == ROWS_DENSE) {
+        n = D;
+    } else if (MODE == ROWS_LIST) {
+        n = max(0, min(*nnz_in, D));
+    } else {
+        const int nwords = D / 64;
+        wpl = (nwords + 63) / 64;
+        int c = 0;
+#pragma unroll 4
+        for (int j = 0; j < wpl; ++j) {
+            const int k = lane * wpl + j;
+            if (k < nwords) c += __popcll(mask[k]);
+        }
+        const int inc = wave_inclusive_scan(c);
+        lane_first = inc - c;
+        n = __builtin_amdgcn_readlane(inc, 63);
+    }
+    SVDP_STAMP(2, 1);
+    const int chunk = chunk_of(n, G);
+    const int lo = min(n, (int)blockIdx.x * chunk);
     const int hi = min(n, lo + chunk);
-    if (lo >= hi) return;
+    const int cnt = hi - lo;
+    if (blockIdx.x == 0 && tid == 0) {
+        if (MODE != ROWS_DENSE) *n_used = n;
+        if (MODE == ROWS_MASK && nnz_out != nullptr) *nnz_out = n;
+    }
+    if (cnt <= 0) return;
+
+    // Phase B walks the chunk in groups of UB rows; the last group is padded with
+    // repeats of the last row whose h is 0, so no loop below needs a tail.
+    const int ngroups = (cnt + UB - 1) / UB;
+    const int padded = ngroups * UB;
+    if (MODE == ROWS_LIST) {
+        for (int q = tid; q < padded; q += ROWS_THREADS) lidx[q] = idx_in[lo + min(q, cnt - 1)];
+    } else if (MODE == ROWS_MASK) {
+        if (wave == 0) {
+            // Lane l knows where its words start in the list (lane_first).  Words that
+            // overlap [lo, hi) are handed to the whole wave one at a time: lane j then
+            // looks at bit j, whose list position is the word's start plus the number
+            // of set bits below it.
+            const int nwords = D / 64;
+            int p = lane_first;
+            for (int j = 0; j < wpl; ++j) {
+                const int k = lane * wpl + j;
+                const uint64_t w = k < nwords ? mask[k] : 0ull;
+                const int pc = __popcll(w);
+                const bool overlaps = pc > 0 && p < hi && p + pc > lo;
+                uint64_t todo = __ballot(overlaps);
+                while (todo != 0ull) {
+                    const int src = __ffsll((unsigned long long)todo) - 1;
+                    todo &= todo - 1ull;
+                    const uint32_t wlo = __builtin_amdgcn_readlane((uint32_t)w, src);
+                    const uint32_t whi = __builtin_amdgcn_readlane((uint32_t)(w >> 32), src);
+                    const int pk = __builtin_amdgcn_readlane(p, src);
+                    const uint64_t wk = ((uint64_t)whi << 32) | wlo;
+                    if ((wk >> lane) & 1ull) {
+                        const int pos = pk + __popcll(wk & ((1ull << lane) - 1ull));
+                        if (pos >= lo && pos < hi) lidx[pos - lo] = (src * wpl + j) * 64 + lane;
+                    }
+                }
+                p += pc;
+            }
+            // same wave, LDS is in order: the last real entry is visible to the padding
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (lane < padded - cnt) lidx[cnt + lane] = lidx[cnt - 1];
+        }
+    }
+    for (int i = cnt + tid; i < padded; i += ROWS_THREADS)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) hs[b * max_chunk + i] = 0.f;
+    __syncthreads();
+    SVDP_STAMP(2, 2);
+    if (MODE == ROWS_MASK && idx_out != nullptr)
+        for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
+
     const bool drelu = (flags & 1u) != 0;
     const bool revalidate = (flags & 2u) != 0;
+    auto row_of = [&](int q) -> size_t {
+        return MODE == ROWS_DENSE ? (size_t)(lo + min(q, cnt - 1)) : (size_t)lidx[q];
+    };
 
-    for (int i = tid; i < NB * d; i += ROWS_THREADS) {
-        const int b = i / d;
-        xs[i] = b < B ? to_f32(x[i]) : 0.f;
+    // ---- request the first group of W_downT rows for this thread's first column group ----
+    uint4 cur[UB];
+    const bool preload = !revalidate && tid < nvec;
+    if (preload) {
+#pragma unroll
+        for (int k = 0; k < UB; ++k) cur[k] = load_raw(WdT + row_of(k) * d + (size_t)tid * VEC);
     }
-    __syncthreads();
 
-    const int nvec = d / VEC;
-    for (int q = lo + wave; q < hi; q += ROWS_THREADS / 64) {
-        const size_t row = DENSE ? (size_t)q : (size_t)idx[q];
-        const W *g = Wg + row * d;
-        const W *u = Wu + row * d;
+    // ---- phase A ----
+    const int nfull = nvec / (64 * UA);
+    for (int q = wave; q < cnt; q += ROWS_WAVES) {
+        const size_t row = row_of(q);
+        const W *g = Wg + row * d + (size_t)lane * VEC;
+        const W *u = Wu + row * d + (size_t)lane * VEC;
         float ag[NB], au[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) ag[b] = au[b] = 0.f;
-#pragma unroll 2
-        for (int v = lane; v < nvec; v += 64) {
-            float wg[VEC], wu[VEC];
-            load_vec(g + v * VEC, wg);
-            load_vec(u + v * VEC, wu);
+        for (int it = 0; it < nfull; ++it) {
+            uint4 rg[UA], ru[UA];
+#pragma unroll
+            for (int k = 0; k < UA; ++k) {
+                rg[k] = load_raw(g + (size_t)(it * UA + k) * 64 * VEC);
+                ru[k] = load_raw(u + (size_t)(it * UA + k) * 64 * VEC);
+            }
+#pragma unroll
+            for (int k = 0; k < UA; ++k) {
+                const int v = lane + (it * UA + k) * 64;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const uint4 xv = xraw[b * nvec + v];
+                    ag[b] = dot_raw(rg[k], xv, ag[b], (const W *)nullptr);
+                    au[b] = dot_raw(ru[k], xv, au[b], (const W *)nullptr);
+                }
+            }
+        }
+        for (int v = lane + nfull * UA * 64; v < nvec; v += 64) {       // ragged tail of the row
+            const uint4 rg = load_raw(Wg + row * d + (size_t)v * VEC);
+            const uint4 ru = load_raw(Wu + row * d + (size_t)v * VEC);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const float *xb = xs + b * d + v * VEC;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    ag[b] = fmaf(wg[e], xb[e], ag[b]);
-                    au[b] = fmaf(wu[e], xb[e], au[b]);
-                }
+                const uint4 xv = xraw[b * nvec + v];
+                ag[b] = dot_raw(rg, xv, ag[b], (const W *)nullptr);
+                au[b] = dot_raw(ru, xv, au[b], (const W *)nullptr);
             }
         }
 #pragma unroll
@@ -288,35 +484,65 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows(const W *__restrict__ Wg,
             if (lane == 0) {
                 const float gp = fmaxf(gs, 0.f);
                 const float uu = drelu ? fmaxf(us, 0.f) : us;
-                hs[b * max_chunk + (q - lo)] = gp * uu;
+                hs[b * max_chunk + q] = gp * uu;
             }
         }
     }
+    SVDP_STAMP(2, 3);
     __syncthreads();
+    SVDP_STAMP(2, 4);
 
+    // ---- phase B ----
     for (int v = tid; v < nvec; v += ROWS_THREADS) {
         float acc[NB][VEC];
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[b][e] = 0.f;
-#pragma unroll 4
-        for (int q = lo; q < hi; ++q) {
-            float h[NB];
-            bool any = false;
+        const W *colp = WdT + (size_t)v * VEC;
+        if (revalidate) {
+            // sequential pipeline: a row whose gate was <= 0 for every token is not read
+            for (int q = 0; q < cnt; ++q) {
+                float h[NB];
+                bool any = false;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                h[b] = hs[b * max_chunk + (q - lo)];
-                any = any || (h[b] != 0.f);
+                for (int b = 0; b < NB; ++b) {
+                    h[b] = hs[b * max_chunk + q];
+                    any = any || (h[b] != 0.f);
+                }
+                if (!any) continue;
+                float w[VEC];
+                load_vec(colp + row_of(q) * d, w);
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc[b][e] = fmaf(h[b], w[e], acc[b][e]);
             }
-            if (revalidate && !any) continue;
-            const size_t row = DENSE ? (size_t)q : (size_t)idx[q];
-            float w[VEC];
-            load_vec(WdT + row * d + v * VEC, w);
+        } else {
+            if (v != tid) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
+                for (int k = 0; k < UB; ++k) cur[k] = load_raw(colp + row_of(k) * d);
+            }
+            for (int gq = 0; gq < ngroups; ++gq) {
+                uint4 nxt[UB];
+                if (gq + 1 < ngroups) {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[b][e] = fmaf(h[b], w[e], acc[b][e]);
+                    for (int k = 0; k < UB; ++k) nxt[k] = load_raw(colp + row_of((gq + 1) * UB + k) * d);
+                }
+#pragma unroll
+                for (int k = 0; k < UB; ++k) {
+                    float w[VEC];
+                    widen(cur[k], w, (const W *)nullptr);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        const float h = hs[b * max_chunk + gq * UB + k];
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) acc[b][e] = fmaf(h, w[e], acc[b][e]);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < UB; ++k) cur[k] = nxt[k];
+            }
         }
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
@@ -326,33 +552,64 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows(const W *__restrict__ Wg,
                 out[e4] = make_float4(acc[b][4 * e4], acc[b][4 * e4 + 1], acc[b][4 * e4 + 2], acc[b][4 * e4 + 3]);
         }
     }
+    SVDP_STAMP(2, 5);
+    SVDP_STAMP_CLK(2, 7);
 }
 
 // ---------------------------------------------------------------------------
-// y[b][:] = sum over the blocks of k_rows that had work, in block order
-// (second stage of the deterministic down-projection reduction, App. C).
+// y[b][:] = sum over the blocks of k_rows that had work (second stage of the
+// deterministic down-projection reduction, App. C).
+// A block owns RED_COLS float4 columns of one token; the list of partials is
+// cut into RED_SEGS contiguous segments summed by different threads (so all
+// loads are in flight at once) and the segment sums are combined by a
+// radix-4 tree through LDS.  The order depends only on the number of partials.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_reduce_y(const float *__restrict__ ypart,
-                                                  const int32_t *__restrict__ nnz_p, int n_fixed, int D,
-                                                  int G, int NB, int B, int d, float *__restrict__ y)
+__global__ __launch_bounds__(RED_COLS *RED_SEGS) void k_reduce_y(const float *__restrict__ ypart,
+                                                                 const int32_t *__restrict__ n_ptr, int n_fixed,
+                                                                 int D, int G, int NB, int B, int d,
+                                                                 float *__restrict__ y)
 {
-    int n = nnz_p != nullptr ? *nnz_p : n_fixed;
+    __shared__ float4 red[RED_SEGS][RED_COLS];
+    SVDP_STAMP(3, 0);
+    int n = n_ptr != nullptr ? *n_ptr : n_fixed;
     n = max(0, min(n, D));
     const int chunk = chunk_of(n, G);
     const int gact = n > 0 ? (n + chunk - 1) / chunk : 0;
     const int vpt = d / 4;
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    if (t >= B * vpt) return;
-    const int b = t / vpt, v = t % vpt;
-    const float4 *src = reinterpret_cast<const float4 *>(ypart) + (size_t)b * vpt + v;
-    const size_t stride = (size_t)NB * vpt;
+    const int bpt = (vpt + RED_COLS - 1) / RED_COLS;
+    const int b = blockIdx.x / bpt;
+    const int c = threadIdx.x % RED_COLS, seg = threadIdx.x / RED_COLS;
+    const int v = (blockIdx.x % bpt) * RED_COLS + c;
+    const int per = (gact + RED_SEGS - 1) / RED_SEGS;
+    const int g0 = seg * per, g1 = min(gact, g0 + per);
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 8
-    for (int g = 0; g < gact; ++g) {
-        const float4 p = src[(size_t)g * stride];
-        s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    if (v < vpt) {
+        const float4 *src = reinterpret_cast<const float4 *>(ypart) + (size_t)b * vpt + v;
+        const size_t stride = (size_t)NB * vpt;
+#pragma unroll 4
+        for (int g = g0; g < g1; ++g) {
+            const float4 p = src[(size_t)g * stride];
+            s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+        }
     }
-    reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = s;
+    red[seg][c] = s;
+    __syncthreads();
+    for (int width = RED_SEGS / 4; width >= 1; width /= 4) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (seg < width) {
+            t = red[4 * seg][c];
+#pragma unroll
+            for (int q = 1; q < 4; ++q) {
+                const float4 p = red[4 * seg + q][c];
+                t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+            }
+        }
+        __syncthreads();
+        if (seg < width) red[seg][c] = t;
+        __syncthreads();
+    }
+    if (seg == 0 && v < vpt) reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = red[0][c];
+    SVDP_STAMP(3, 1);
 }
 
 // ---------------------------------------------------------------------------
