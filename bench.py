@@ -3,15 +3,18 @@
 
 A "step" is one pass of the whole hot path - predictor scores, union mask, index
 list, gate/up on the active rows, down projection - for one batch of decode
-tokens of one layer.  K steps over K different seeded tokens are captured in one
-HIP graph and replayed; the layer's weights rotate over several copies at
-distinct addresses so that a step never finds its rows in the 256 MB last-level
-cache ("cold" mode, the one the roofline fraction is quoted on).
+tokens of one layer (for --workload stack: through all layers of the stack, glue
+included).  K steps over K different seeded tokens are captured in one HIP graph
+and replayed; a single layer's weights rotate over several copies at distinct
+addresses so that a step never finds its rows in the 256 MB last-level cache
+("cold" mode, the one the roofline fraction is quoted on; the stack is cold by
+construction).
 
 Prints ONE JSON line.  `value` is microseconds per token per layer (lower is
-better); `roofline` is the algorithmic HBM bytes of the step divided by the
-measured time against the 8 TB/s peak; `cpu_baseline` is the CPU oracle timed on
-a bounded sample of the same tokens on this machine's host cores.
+better); `roofline` is the algorithmic HBM bytes of a step (summed from the
+measured list length of every step) divided by the measured time, against the
+8 TB/s peak; `cpu_baseline` is the CPU oracle timed on a bounded sample of the
+same tokens on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -32,20 +35,24 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1024)
     ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "13b", "mistral"])
+    ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "13b", "mistral", "stack"])
     ap.add_argument("--rank", type=int, default=0, help="predictor rank (0 = the workload's default)")
     ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--layers", type=int, default=32, help="layers of --workload stack")
     ap.add_argument("--copies", type=int, default=16, help="weight copies rotated through (1 = hot cache)")
     ap.add_argument("--reps", type=int, default=5, help="graph replays; the median is reported")
     ap.add_argument("--flags", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
 
 
 def time_graph(torch, fn_step, n_steps, warmup, reps, use_graph=True):
-    """Median milliseconds for n_steps calls of fn_step(k) (k = 0..n_steps-1)."""
+    """Median milliseconds for n_steps calls of fn_step(k) (k = 0..n_steps-1), HIP events on the
+    stream the kernels are launched on."""
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         for k in range(min(warmup, n_steps)):
@@ -76,7 +83,7 @@ def time_graph(torch, fn_step, n_steps, warmup, reps, use_graph=True):
     return times[len(times) // 2], times
 
 
-def cpu_baseline(layer, X, B, seconds):
+def cpu_baseline_layer(layer, X, B, seconds):
     """The oracle as it stands, timed on the host cores over a bounded sample of the tokens."""
     import oracle
 
@@ -94,19 +101,7 @@ def cpu_baseline(layer, X, B, seconds):
             "sample": f"first {n} tokens of the timed stream, batch {B}, {dt:.1f} s of wall time"}
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-
-    from paper_2603_14110_amd import binding, cost, synth
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    binding.lib()
+def run_layer(a, torch, np, binding, cost, synth):
     over = {"r": a.rank} if a.rank else {}
     spec = synth.workload(a.workload, **over)
     B, K = a.batch, a.steps
@@ -130,41 +125,120 @@ def main():
     nnz = NNZ.cpu().numpy().reshape(-1).astype(np.int64)
     Kd = min(K, 128)
     ms_dense, _ = time_graph(torch, dense_step, Kd, min(a.warmup, 8), max(3, a.reps // 2), not a.no_graph)
+    bytes_mean = float(np.mean([cost.bytes_sparse(spec.d, spec.D, spec.r, int(n), B, w) for n in nnz]))
+    res = dict(
+        us_step=ms * 1e3 / K, us_dense=ms_dense * 1e3 / Kd, bytes_step=bytes_mean,
+        bytes_dense=cost.bytes_dense(spec.d, spec.D, B, w), layers=1, all_ms=all_ms,
+        density=nnz / spec.D,
+        workload=f"{spec.name}-shaped layer d={spec.d} D={spec.D} r={spec.r} batch={B}, {K} decode steps, "
+                 f"~{spec.sparsity:.0%} activation sparsity per token",
+        dtype=spec.dtype, cache_mode="cold" if len(copies) > 1 else "hot", copies=len(copies),
+    )
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_layer(layer, synth.storage_to_f32(X_st, spec.dtype), B, a.cpu_seconds)
+    return res
 
-    us_step = ms * 1e3 / K
-    us_dense = ms_dense * 1e3 / Kd
-    bytes_steps = [cost.bytes_sparse(spec.d, spec.D, spec.r, int(n), B, w) for n in nnz]
-    bytes_mean = float(np.mean(bytes_steps))
-    achieved = bytes_mean / (us_step * 1e-6) / 1e9
-    dense_bytes = cost.bytes_dense(spec.d, spec.D, B, w)
+
+def run_stack(a, torch, np, binding, cost, synth):
+    from paper_2603_14110_amd import stack
+
+    assert a.batch == 1, "the stacked workload is batch 1"
+    over = {"r": a.rank} if a.rank else {}
+    specs = stack.stack_specs(a.layers, base="7b", **over)
+    K = a.steps
+    dev_layers, u_all, L0 = [], [], None
+    for i, sp in enumerate(specs):
+        L = synth.load_or_make(sp)
+        dev_layers.append(binding.DeviceLayer.from_synth(L, flags=a.flags))
+        u_all.append(L.u)
+        if i == 0:
+            L0 = L                      # tokens and the oracle baseline use the first layer
+        del L
+        print(f"[bench] layer {i + 1}/{len(specs)} ready (target sparsity {sp.sparsity:.3f})", file=sys.stderr, flush=True)
+    shifts = [torch.from_numpy((2.0 * u_all[i + 1]).astype(np.float32)).cuda() for i in range(len(specs) - 1)]
+    shifts.append(torch.zeros(specs[0].d, dtype=torch.float32, device="cuda"))
+    st = stack.FFNStack(dev_layers, shifts)
+    X_st = synth.timed_tokens(L0, K)
+    Xd = binding.to_device(X_st, "bf16")
+    NNZ = torch.zeros((K, len(specs), 1), dtype=torch.int32, device="cuda")
+    OUT = torch.zeros((K, specs[0].d), dtype=torch.bfloat16, device="cuda")
+
+    def sparse_step(k):
+        OUT[k].copy_(st.step(Xd[k], nnz=NNZ[k]))
+
+    dense = st.as_dense()
+
+    def dense_step(k):
+        OUT[k].copy_(dense.step(Xd[k]))
+
+    ms, all_ms = time_graph(torch, sparse_step, K, min(a.warmup, 4), a.reps, not a.no_graph)
+    nnz = NNZ.cpu().numpy().reshape(K, len(specs)).astype(np.int64)
+    Kd = min(K, 16)
+    ms_dense, _ = time_graph(torch, dense_step, Kd, 2, 3, not a.no_graph)
+    sp0 = specs[0]
+    per_step = [sum(cost.bytes_sparse(sp0.d, sp0.D, sp0.r, int(n), 1, 2) for n in row) for row in nnz]
+    res = dict(
+        us_step=ms * 1e3 / K, us_dense=ms_dense * 1e3 / Kd, bytes_step=float(np.mean(per_step)),
+        bytes_dense=len(specs) * cost.bytes_dense(sp0.d, sp0.D, 1, 2), layers=len(specs), all_ms=all_ms,
+        density=(nnz / sp0.D).reshape(-1),
+        workload=f"{len(specs)}-layer stack of 7b-shaped layers d={sp0.d} D={sp0.D} r={sp0.r} batch=1, {K} decode "
+                 f"steps, per-layer target sparsity U(0.80,0.95), residual + RMS-norm glue, one HIP graph",
+        dtype="bf16", cache_mode="cold (8.9 GB of weights)", copies=1,
+    )
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_layer(L0, synth.storage_to_f32(X_st, "bf16"), 1, a.cpu_seconds)
+        res["cpu_baseline"]["sample"] += " (first layer of the stack only)"
+    return res
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2603_14110_amd import binding, cost, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    binding.lib()
+    r = (run_stack if a.workload == "stack" else run_layer)(a, torch, np, binding, cost, synth)
+    if a.calib_copy_mb:
+        n = a.calib_copy_mb << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
+    K, B, Lyr = a.steps, a.batch, r["layers"]
+    us_step, us_dense = r["us_step"], r["us_dense"]
+    achieved = r["bytes_step"] / (us_step * 1e-6) / 1e9
+    dens = r["density"]
     out = {
         "metric": "us_per_token_per_layer_sparse_ffn_decode_incl_predictor",
-        "value": us_step / B,
+        "value": us_step / B / Lyr,
         "unit": "us/token/layer",
         "n_gpus": 1,
         "steps": K,
         "warmup": a.warmup,
-        "ms_per_step": ms / K,
+        "ms_per_step": us_step / 1e3,
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 storage, f32 accumulate" if spec.dtype == "bf16" else "f32",
+        "dtype": "bf16" if r["dtype"] == "bf16" else "f32",
         "data": "synthetic",
-        "config": {
-            "workload": f"{spec.name}-shaped layer d={spec.d} D={spec.D} r={spec.r} batch={B}, "
-                        f"{K} decode tokens, ~{spec.sparsity:.0%} activation sparsity",
-            "batch": B,
-            "weight_copies": len(copies),
-            "cache_mode": "cold" if len(copies) > 1 else "hot",
-            "flags": a.flags,
-            "graph": not a.no_graph,
-        },
-        "density_mean": float(nnz.mean() / spec.D),
-        "density_percentiles_0_5_50_95_100": [float(np.percentile(nnz, p) / spec.D) for p in (0, 5, 50, 95, 100)],
+        "config": {"workload": r["workload"], "batch": B, "layers": Lyr, "weight_copies": r["copies"],
+                   "cache_mode": r["cache_mode"], "flags": a.flags, "graph": not a.no_graph,
+                   "storage": "bf16 weights/tokens, f32 accumulate" if r["dtype"] == "bf16" else "f32"},
+        "density_mean": float(dens.mean()),
+        "density_percentiles_0_5_50_95_100": [float(np.percentile(dens, p)) for p in (0, 5, 50, 95, 100)],
         "dense_us_per_step": us_dense,
+        "dense_us_per_token_per_layer": us_dense / B / Lyr,
         "speedup_vs_dense": us_dense / us_step,
-        "dense_achieved_GBs": dense_bytes / (us_dense * 1e-6) / 1e9,
-        "replay_ms_all": all_ms,
+        "dense_achieved_GBs": r["bytes_dense"] / (us_dense * 1e-6) / 1e9,
+        "replay_ms_all": r["all_ms"],
         "roofline": {
             "bound": "hbm",
             "achieved": achieved,
@@ -172,15 +246,15 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": None,
-            "kernel": "whole step (all kernels of svdp_ffn_step)",
-            "algorithmic_bytes_per_step": bytes_mean,
+            "kernel": "whole step: all kernels svdp_ffn_step launches (k_xP, k_scores, k_rows, k_reduce_y), "
+                      "timed together with HIP events around the replayed graph",
+            "algorithmic_bytes_per_step": r["bytes_step"],
         },
-        "paper_context": "paper reports up to 1.8x end-to-end decode-time reduction (RTX 3090, fp16, vLLM) and "
-                         "3.3-4.9x FFN-only speedup at 80-95 % sparsity; no absolute latencies",
+        "paper_context": "the paper reports ratios only: up to 1.8x end-to-end decode-time reduction (RTX 3090, fp16, "
+                         "vLLM) and 3.3-4.9x FFN-only speedup at 80-95 % sparsity (predictor excluded)",
     }
-    if not a.no_cpu_baseline:
-        X = synth.storage_to_f32(X_st, spec.dtype)
-        out["cpu_baseline"] = cpu_baseline(layer, X, B, a.cpu_seconds)
+    if "cpu_baseline" in r:
+        out["cpu_baseline"] = r["cpu_baseline"]
     print(json.dumps(out))
 
 

@@ -1,0 +1,96 @@
+"""GPU parity of a small stack of layers with the benchmark's glue, eager and as a replayed HIP graph."""
+import numpy as np
+import pytest
+
+import parity
+from paper_2603_14110_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def small_stack(oracle):
+    import torch
+    from paper_2603_14110_amd import binding, stack
+
+    assert torch.cuda.is_available()
+    binding.lib()
+    specs = stack.stack_specs(4, base="tiny", seed0=7000, d=512, D=1536, r=48, dtype="bf16", k_dom=24, n_cal=256)
+    layers = [synth.make_layer(sp) for sp in specs]
+    return layers, stack.FFNStack.from_synth(layers), binding, torch
+
+
+def oracle_stack(oracle, layers, x0_f32, teacher=None):
+    """Oracle stack in fp64, activations re-rounded to the storage dtype between layers.
+    Returns the per-layer inputs (as stored), scores, lists and outputs."""
+    dt = layers[0].spec.dtype
+    xs, out = [np.asarray(x0_f32, dtype=np.float32)], []
+    for l, L in enumerate(layers):
+        f = {k: L.f32(k) for k in ("W_gate", "W_up", "W_downT", "P", "Q", "b")}
+        s, m, idx, y = oracle.ffn_step(f, xs[l])
+        shift = 2.0 * layers[l + 1].u if l + 1 < len(layers) else np.zeros(L.spec.d)
+        xn = oracle.stack_glue(xs[l].astype(np.float64), y[0], shift)
+        xs.append(synth.storage_to_f32(synth.to_storage(xn, dt), dt))
+        out.append((s, idx, y))
+    return xs, out
+
+
+def test_stack_teacher_forced_and_free_running(small_stack, oracle):
+    layers, st, binding, torch = small_stack
+    L0 = layers[0]
+    X = synth.storage_to_f32(synth.timed_tokens(L0, 6), "bf16")
+    Xd = binding.to_device(synth.timed_tokens(L0, 6), "bf16")
+    for t in range(6):
+        xs, out = oracle_stack(oracle, layers, X[t])
+        # teacher-forced: the oracle's input of layer l goes into GPU layer l
+        for l, L in enumerate(layers):
+            D = L.spec.D
+            xin = binding.to_device(synth.to_storage(xs[l], "bf16"), "bf16")
+            mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+            idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+            nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+            y = binding.ffn_step(st.layers[l], xin, mask=mask, idx=idx, nnz=nnz)
+            lst = parity.check_mask_and_idx(out[l][0], mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+            f = {k: L.f32(k) for k in ("W_gate", "W_up", "W_downT")}
+            y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], xs[l], lst)
+            parity.check_y(y.cpu().numpy(), y_ref, "bf16")
+            xn = binding.stack_glue(xin, y, st.shifts[l]).float().cpu().numpy()
+            ref = xs[l + 1]
+            assert np.all(np.abs(xn - ref) <= 2.0 ** -7 * np.maximum(np.abs(ref), 1.0))
+        # free-running: the whole stack on the GPU; compared loosely (a borderline neuron may flip)
+        got = st.step(Xd[t]).float().cpu().numpy()
+        assert np.linalg.norm(got - xs[-1]) <= 0.05 * np.linalg.norm(xs[-1])
+
+
+def test_stack_graph_replay_matches_eager(small_stack):
+    """The whole step captured in one HIP graph; every replay (with eager work in between)
+    must reproduce the eager result bit for bit."""
+    layers, st, binding, torch = small_stack
+    Xd = binding.to_device(synth.timed_tokens(layers[0], 5), "bf16")
+    eager = [st.step(Xd[t]).clone() for t in range(5)]
+    xin = torch.zeros_like(Xd[0])
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        st.step(xin)
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            out = st.step(xin)
+    for rnd in range(3):
+        for t in range(5):
+            xin.copy_(Xd[t])
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager[t]), (rnd, t)
+            assert torch.equal(st.step(Xd[t]), eager[t])     # eager work between replays
+
+
+def test_dense_stack_close_to_sparse(small_stack):
+    layers, st, binding, torch = small_stack
+    Xd = binding.to_device(synth.timed_tokens(layers[0], 3), "bf16")
+    for t in range(3):
+        a = st.step(Xd[t]).float().clone()
+        b = st.as_dense().step(Xd[t]).float()
+        # the predictor keeps ~99 % of the truly active neurons: outputs are close, not equal
+        assert torch.linalg.norm(a - b) <= 0.25 * torch.linalg.norm(b)
