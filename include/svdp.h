@@ -17,7 +17,9 @@
  *    enqueued and a status other than SVDP_OK is returned;
  *  - `ws` is a device scratch buffer of at least svdp_workspace_bytes() bytes,
  *    256-byte aligned, owned by the caller; its contents are undefined between
- *    calls; two calls that may overlap in time need distinct workspaces;
+ *    calls; two calls that may overlap in time need distinct workspaces (at
+ *    most 64 distinct workspace addresses per process get the persistent step
+ *    kernel, further ones use the kernel sequence);
  *  - B is the number of tokens decoded together, 1 <= B <= SVDP_MAX_BATCH; all
  *    tokens of a batch share ONE mask (the union of their masks) and one index
  *    list, and every token is computed exactly over that list;
@@ -126,6 +128,22 @@ svdp_status svdp_dense_ffn(const svdp_layer *layer, const void *x, int32_t B,
 svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, float *y,
                           uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out,
                           void *ws, size_t ws_bytes, void *stream);
+
+/* How svdp_ffn_step runs.  persistent != 0 (the default): one persistent launch,
+ * one block per compute unit, whose stages hand their results over through
+ * global memory and bounded waits; it needs every block resident at once, so the
+ * GPU must not be shared with other work while it runs.  persistent == 0: a
+ * sequence of four ordinary launches.  Both give the same mask and index list;
+ * y agrees to rounding (the partial sums are cut differently).  Shapes the
+ * persistent kernel cannot hold fall back to the sequence by themselves.
+ * spin_limit > 0 sets the number of polls after which a stage wait gives up
+ * (the step then finishes with undefined output and the timeout is recorded).
+ * Process-wide; call it while no step is in flight.                             */
+void svdp_set_step_mode(int32_t persistent, int32_t spin_limit);
+
+/* Number of workspaces on which a persistent step gave up waiting since the last
+ * call; clears the record.  Synchronises the device: not for use under capture. */
+svdp_status svdp_step_timeouts(int32_t *count);
 
 /* Glue between stacked layers used by the stacked benchmark (not from the
  * paper): v = x + y; x_next = v / sqrt(mean(v^2) + eps) + shift, rounded to

@@ -22,7 +22,8 @@ MAX_BATCH = 8
 
 EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
-    "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version",
+    "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version", "svdp_set_step_mode",
+    "svdp_step_timeouts",
 ]
 
 
@@ -67,6 +68,10 @@ def lib() -> ctypes.CDLL:
     L.svdp_status_string.restype = ctypes.c_char_p
     L.svdp_version.argtypes = []
     L.svdp_version.restype = ctypes.c_char_p
+    L.svdp_set_step_mode.argtypes = [i32, i32]
+    L.svdp_set_step_mode.restype = None
+    L.svdp_step_timeouts.argtypes = [ctypes.POINTER(ctypes.c_int32)]
+    L.svdp_step_timeouts.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -218,6 +223,16 @@ def stack_glue(x: torch.Tensor, y: torch.Tensor, shift: torch.Tensor, eps: float
     _check(lib().svdp_stack_glue(_ptr(x), _ptr(y), _ptr(shift), d, dt, float(eps), _ptr(out), _stream()),
            "svdp_stack_glue")
     return out
+
+
+def set_step_mode(persistent: bool, spin_limit: int = 0) -> None:
+    lib().svdp_set_step_mode(1 if persistent else 0, int(spin_limit))
+
+
+def step_timeouts() -> int:
+    n = ctypes.c_int32(0)
+    _check(lib().svdp_step_timeouts(ctypes.byref(n)), "svdp_step_timeouts")
+    return int(n.value)
 
 
 def version() -> str:

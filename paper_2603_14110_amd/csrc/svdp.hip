@@ -5,6 +5,11 @@
 #include <hip/hip_runtime.h>
 
 #include "svdp_kernels.h"
+#include "svdp_fused.h"
+
+#include <atomic>
+#include <mutex>
+#include <vector>
 
 namespace {
 
@@ -46,7 +51,7 @@ svdp_status check_layer(const svdp_layer *L, bool need_pred, bool need_ffn)
 }
 
 // Workspace layout (all offsets 256-byte aligned):
-//   tpart [XP_MAX_BLOCKS][NB][r] f32 | mask [D/64] u64 | idx [D] i32 | nnz i32 | ypart [ROWS_GRID][NB][d] f32
+//   tpart [XP_MAX_BLOCKS + 1][NB][r] f32 | mask [D/64] u64 | idx [D] i32 | nnz i32 | ypart [ROWS_GRID][NB][d] f32
 struct Workspace {
     float *tpart;
     uint64_t *mask;
@@ -62,7 +67,7 @@ Workspace carve(void *base, int d, int D, int r, int NB)
     char *p = static_cast<char *>(base);
     size_t off = 0;
     w.tpart = reinterpret_cast<float *>(p + off);
-    off += align_up((size_t)XP_MAX_BLOCKS * NB * r * 4);
+    off += align_up((size_t)(XP_MAX_BLOCKS + 1) * NB * r * 4);     // partials, then the finished t
     w.mask = reinterpret_cast<uint64_t *>(p + off);
     off += align_up((size_t)D / 64 * 8);
     w.idx = reinterpret_cast<int32_t *>(p + off);
@@ -111,7 +116,10 @@ svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, i
     const int d = L->d, r = L->r;
     const int nt = (d + XP_ROWS - 1) / XP_ROWS;           // <= XP_MAX_BLOCKS since d <= 16384
     const int ncs = (r + XP_COLS - 1) / XP_COLS;
-    const size_t lds = ((size_t)NB * XP_ROWS + (size_t)(XP_THREADS / (XP_COLS / VEC)) * NB * XP_COLS) * 4;
+    const size_t outs = (size_t)NB * XP_COLS;
+    const size_t parts = XP_THREADS / outs >= 1 ? XP_THREADS / outs : 1;
+    const size_t nsub = XP_THREADS / (XP_COLS / VEC);
+    const size_t lds = ((size_t)NB * XP_ROWS + nsub * (outs + 1) + parts * outs) * 4;
     static int granted = 64 * 1024;
     if (allow_lds(k_xP<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((k_xP<W, NB>), dim3(nt, ncs), dim3(XP_THREADS), lds, st, static_cast<const W *>(L->P),
@@ -124,11 +132,12 @@ template <typename W, int NB, int LPR_LOG2>
 svdp_status launch_scores_lpr(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
                               uint64_t *mask_out, hipStream_t st)
 {
-    const size_t tsp = (size_t)NB * L->r > (size_t)SC_THREADS * 4 ? (size_t)NB * L->r : (size_t)SC_THREADS * 4;
+    constexpr int THREADS = NB <= 2 ? 1024 : 256;
+    const size_t tsp = (size_t)NB * L->r > (size_t)THREADS * 4 ? (size_t)NB * L->r : (size_t)THREADS * 4;
     const size_t lds = ((size_t)NB * L->r + (size_t)NB * SC_SLAB + tsp) * 4;
     static int granted = 64 * 1024;
-    if (allow_lds(k_scores<W, NB, LPR_LOG2>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_scores<W, NB, LPR_LOG2>), dim3(L->D / SC_SLAB), dim3(SC_THREADS), lds, st,
+    if (allow_lds(k_scores<W, NB, LPR_LOG2, THREADS>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_scores<W, NB, LPR_LOG2, THREADS>), dim3(L->D / SC_SLAB), dim3(THREADS), lds, st,
                        static_cast<const W *>(L->Q), L->b, tpart, nt, B, L->D, L->r, s_out, mask_out);
     return hip_status(hipSuccess);
 }
@@ -150,11 +159,12 @@ svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_
                         hipStream_t st)
 {
     const int d = L->d, D = L->D;
-    const int max_chunk = ((D + ROWS_GRID - 1) / ROWS_GRID + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
+    const int grid = NB >= 4 ? ROWS_GRID / 2 : ROWS_GRID;     // big batches: halve the partial-y traffic
+    const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
     const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
     static int granted = 64 * 1024;
     if (allow_lds(k_rows<W, NB, MODE>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_rows<W, NB, MODE>), dim3(ROWS_GRID), dim3(ROWS_THREADS), lds, st,
+    hipLaunchKernelGGL((k_rows<W, NB, MODE>), dim3(grid), dim3(ROWS_THREADS), lds, st,
                        static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
                        static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, mask, idx_in, nnz_in,
                        idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart);
@@ -163,13 +173,109 @@ svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_
     const int vpt = d / 4;
     const int blocks = B * ((vpt + RED_COLS - 1) / RED_COLS);
     hipLaunchKernelGGL(k_reduce_y, dim3(blocks), dim3(RED_COLS * RED_SEGS), 0, st, w.ypart,
-                       MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, ROWS_GRID, NB, B, d, y);
+                       MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, grid, NB, B, d, y);
     return hip_status(hipSuccess);
 }
 
 svdp_status launch_compact(const uint64_t *mask, int D, int32_t *idx, int32_t *nnz, hipStream_t st)
 {
     hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(SCAN_THREADS), 0, st, mask, D / 64, idx, nnz);
+    return hip_status(hipSuccess);
+}
+
+// ---- the single persistent kernel ----
+// Control blocks live in static device memory (zero at load, zero again after every
+// launch); one slot per workspace address seen by this process.
+__device__ __align__(256) uint32_t g_step_ctrl[CTRL_SLOTS * CTRL_WORDS];
+
+std::atomic<int> g_fused_mode{0};            // 1: persistent kernel when supported, 0: kernel sequence
+std::atomic<int> g_spin_limit{400000};       // polls before a stage wait gives up
+std::mutex g_slot_mutex;
+std::vector<const void *> g_slots;
+uint32_t *g_ctrl_base = nullptr;
+int g_num_cus = 0;
+
+bool fused_setup()
+{
+    if (g_ctrl_base != nullptr) return true;
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_step_ctrl)) != hipSuccess || p == nullptr) {
+        (void)hipGetLastError();
+        return false;
+    }
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        return false;
+    }
+    g_num_cus = cus;
+    g_ctrl_base = static_cast<uint32_t *>(p);
+    return true;
+}
+
+// control block of a workspace, or nullptr when none is free
+uint32_t *ctrl_for(const void *ws)
+{
+    std::lock_guard<std::mutex> lock(g_slot_mutex);
+    if (!fused_setup()) return nullptr;
+    for (size_t i = 0; i < g_slots.size(); ++i)
+        if (g_slots[i] == ws) return g_ctrl_base + i * CTRL_WORDS;
+    if (g_slots.size() >= (size_t)CTRL_SLOTS) return nullptr;
+    g_slots.push_back(ws);
+    return g_ctrl_base + (g_slots.size() - 1) * CTRL_WORDS;
+}
+
+inline int fused_max_chunk(int D, int G) { return ((D + G - 1) / G + ROWS_UB - 1) / ROWS_UB * ROWS_UB; }
+
+template <typename W, int NB>
+size_t fused_lds_bytes(const svdp_layer *L, int G)
+{
+    constexpr int VEC = Elem<W>::VEC;
+    const size_t s1 = (size_t)(256 / (XP_COLS / VEC)) * NB * XP_COLS * 4;
+    const size_t tsp = (size_t)NB * L->r > (size_t)FUSED_THREADS * 4 ? (size_t)NB * L->r : (size_t)FUSED_THREADS * 4;
+    const size_t s2 = ((size_t)NB * L->r + (size_t)NB * SC_SLAB + tsp) * 4;
+    const int mc = fused_max_chunk(L->D, G);
+    const size_t s3 = ((size_t)L->D / 64 + 2) * 8 + ((size_t)NB * mc + mc) * 4;
+    const size_t s4 = (size_t)FUSED_THREADS * 16;
+    size_t scratch = s1 > s2 ? s1 : s2;
+    scratch = scratch > s3 ? scratch : s3;
+    scratch = scratch > s4 ? scratch : s4;
+    return (size_t)NB * L->d * sizeof(W) + scratch;
+}
+
+// SVDP_ERR_UNSUPPORTED means "use the kernel sequence instead"
+template <typename W, int NB>
+svdp_status run_step_fused(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
+                           int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
+{
+    constexpr int VEC = Elem<W>::VEC;
+    uint32_t *ctrl = ctrl_for(ws_base);
+    if (ctrl == nullptr) return SVDP_ERR_UNSUPPORTED;
+    const int G = g_num_cus < ROWS_GRID ? g_num_cus : ROWS_GRID;
+    if (L->D / 64 > 4096) return SVDP_ERR_UNSUPPORTED;
+    const size_t lds = fused_lds_bytes<W, NB>(L, G);
+    if (lds > 160 * 1024) return SVDP_ERR_UNSUPPORTED;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_step_fused<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    static int resident = -1;      // blocks of this kernel one CU can hold (1024 threads each)
+    if (resident < 0) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step_fused<W, NB>, FUSED_THREADS, lds) != hipSuccess) {
+            (void)hipGetLastError();
+            nb = 0;
+        }
+        resident = nb;
+    }
+    if (resident < 1) return SVDP_ERR_UNSUPPORTED;
+    const int cg = L->r / VEC;
+    int lpr_log2 = 3;
+    while ((1 << lpr_log2) < cg && lpr_log2 < 6) ++lpr_log2;
+    hipLaunchKernelGGL((k_step_fused<W, NB>), dim3(G), dim3(FUSED_THREADS), lds, st, static_cast<const W *>(L->P),
+                       static_cast<const W *>(L->Q), L->b, static_cast<const W *>(L->W_gate),
+                       static_cast<const W *>(L->W_up), static_cast<const W *>(L->W_downT), static_cast<const W *>(x),
+                       B, L->d, L->D, L->r, lpr_log2, L->flags, w.tpart, w.mask, w.ypart, fused_max_chunk(L->D, G), y,
+                       mask_out, idx_out, nnz_out, ctrl, g_spin_limit.load());
     return hip_status(hipSuccess);
 }
 
@@ -202,13 +308,26 @@ svdp_status run_predict(const svdp_layer *L, const void *x, int B, float *s, uin
     int nt = 0;
     svdp_status e = launch_xP<W, NB>(L, x, B, w.tpart, &nt, st);
     if (e != SVDP_OK) return e;
+    if (NB >= 4 && nt > 1) {
+        // finish t once instead of in every score block
+        const int count = NB * L->r;
+        float *t = w.tpart + (size_t)XP_MAX_BLOCKS * NB * L->r;
+        hipLaunchKernelGGL(k_tsum, dim3((count + 255) / 256), dim3(256), 0, st, w.tpart, nt, count, t);
+        e = hip_status(hipSuccess);
+        if (e != SVDP_OK) return e;
+        return launch_scores<W, NB>(L, t, 1, B, s, mask, st);
+    }
     return launch_scores<W, NB>(L, w.tpart, nt, B, s, mask, st);
 }
 
 template <typename W, int NB>
 svdp_status run_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
-                     int32_t *nnz_out, const Workspace &w, hipStream_t st)
+                     int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
 {
+    if (g_fused_mode.load() != 0) {
+        const svdp_status f = run_step_fused<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st);
+        if (f != SVDP_ERR_UNSUPPORTED) return f;
+    }
     uint64_t *mask = mask_out ? mask_out : w.mask;
     svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st);
     if (e != SVDP_OK) return e;
@@ -229,9 +348,9 @@ svdp_status dispatch_dense(const svdp_layer *L, const void *x, int B, float *y, 
     SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, ROWS_DENSE>(L, x, B, nullptr, nullptr, nullptr, nullptr, nullptr, w, y, st)));
 }
 svdp_status dispatch_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out,
-                          int32_t *idx_out, int32_t *nnz_out, const Workspace &w, hipStream_t st)
+                          int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
 {
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (run_step<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, st)));
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (run_step<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st)));
 }
 
 inline bool bad_batch(int B) { return B < 1 || B > SVDP_MAX_BATCH; }
@@ -306,7 +425,7 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_step(layer, x, B, y, mask_out, idx_out, nnz_out, w, static_cast<hipStream_t>(stream));
+    return dispatch_step(layer, x, B, y, mask_out, idx_out, nnz_out, w, ws, static_cast<hipStream_t>(stream));
 }
 
 svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift, int32_t d, int32_t dtype, float eps,
@@ -337,7 +456,33 @@ const char *svdp_status_string(svdp_status st)
     return "unknown status";
 }
 
-const char *svdp_version(void) { return "0.1"; }
+const char *svdp_version(void) { return "0.2"; }
+
+void svdp_set_step_mode(int32_t persistent, int32_t spin_limit)
+{
+    g_fused_mode.store(persistent != 0 ? 1 : 0);
+    if (spin_limit > 0) g_spin_limit.store(spin_limit);
+}
+
+svdp_status svdp_step_timeouts(int32_t *count)
+{
+    if (count == nullptr) return SVDP_ERR_INVALID_ARG;
+    *count = 0;
+    std::lock_guard<std::mutex> lock(g_slot_mutex);
+    if (g_ctrl_base == nullptr) return SVDP_OK;          // the persistent kernel never ran
+    if (hipDeviceSynchronize() != hipSuccess) return SVDP_ERR_HIP;
+    for (size_t i = 0; i < g_slots.size(); ++i) {
+        uint32_t flag = 0;
+        uint32_t *p = g_ctrl_base + i * CTRL_WORDS + CTRL_ERROR;
+        if (hipMemcpy(&flag, p, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return SVDP_ERR_HIP;
+        if (flag != 0) {
+            *count += 1;
+            flag = 0;
+            if (hipMemcpy(p, &flag, sizeof(flag), hipMemcpyHostToDevice) != hipSuccess) return SVDP_ERR_HIP;
+        }
+    }
+    return SVDP_OK;
+}
 
 #ifdef SVDP_TRACE
 // Debug builds only: copy the phase time stamps to the host (synchronises).

@@ -12,7 +12,6 @@ namespace svdp {
 constexpr int XP_THREADS = 256;      // k_xP block
 constexpr int XP_ROWS = 256;         // rows of P per k_xP block
 constexpr int XP_COLS = 32;          // columns of P per k_xP block
-constexpr int SC_THREADS = 1024;     // k_scores block
 constexpr int SC_SLAB = 64;          // neurons per k_scores block = one mask word
 constexpr int ROWS_THREADS = 512;    // k_rows block
 constexpr int ROWS_WAVES = ROWS_THREADS / 64;
@@ -28,7 +27,7 @@ constexpr int RED_SEGS = 256;        // k_reduce_y: segments of the partial list
 // of P [d][r] and writes tpart[i][b][its columns].  A thread owns one 16-byte
 // column group and every NSUB-th row of the tile; its loads of P are issued
 // before x is staged, and the NSUB row-partials are added through LDS in order.
-// Dynamic LDS: NB*XP_ROWS + NSUB*NB*XP_COLS floats.
+// Dynamic LDS: NB*XP_ROWS + NSUB*(NB*XP_COLS + 1) + PARTS*NB*XP_COLS floats.
 // ---------------------------------------------------------------------------
 template <typename W, int NB>
 __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, const W *__restrict__ x,
@@ -40,7 +39,7 @@ __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, cons
     constexpr int RPT = XP_ROWS / NSUB;        // rows per thread
     extern __shared__ float smem[];
     float *xs = smem;                          // [NB][XP_ROWS]
-    float *red = smem + NB * XP_ROWS;          // [NSUB][NB][XP_COLS]
+    float *red = smem + NB * XP_ROWS;          // [NSUB][NB*XP_COLS + 1] (odd stride: no bank conflicts)
     const int tid = threadIdx.x;
     const int j0 = blockIdx.x * XP_ROWS;
     const int c0 = blockIdx.y * XP_COLS;
@@ -55,9 +54,18 @@ __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, cons
         const int j = j0 + sub + k * NSUB;
         if (colok && j < d) raw[k] = load_raw(P + (size_t)j * r + col);
     }
-    for (int i = tid; i < NB * XP_ROWS; i += XP_THREADS) {
-        const int b = i / XP_ROWS, j = j0 + i % XP_ROWS;
-        xs[i] = (b < B && j < d) ? to_f32(x[(size_t)b * d + j]) : 0.f;
+    // x of the tile's rows, one 16-byte vector per thread and pass (d is a multiple of VEC)
+    for (int i = tid; i < NB * (XP_ROWS / VEC); i += XP_THREADS) {
+        const int b = i / (XP_ROWS / VEC), j = j0 + (i % (XP_ROWS / VEC)) * VEC;
+        float w[VEC];
+        if (b < B && j < d) {
+            load_vec(x + (size_t)b * d + j, w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) w[e] = 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) xs[b * XP_ROWS + (j - j0) + e] = w[e];
     }
     __syncthreads();
 
@@ -83,28 +91,47 @@ __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, cons
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) red[(sub * NB + b) * XP_COLS + cgi * VEC + e] = acc[b][e];
+        for (int e = 0; e < VEC; ++e) red[sub * (NB * XP_COLS + 1) + b * XP_COLS + cgi * VEC + e] = acc[b][e];
     __syncthreads();
-    // two-level sum of the NSUB row phases: PARTS threads per output column first
-    constexpr int PARTS = XP_THREADS / XP_COLS;            // 8
+    // two-level sum of the NSUB row phases (fixed order): the NB*XP_COLS outputs of the
+    // tile are shared out over the block, PARTS threads per output
+    constexpr int OUTS = NB * XP_COLS;
+    constexpr int PARTS = XP_THREADS / OUTS >= 1 ? XP_THREADS / OUTS : 1;
     constexpr int PER = NSUB / PARTS;
-    for (int b = 0; b < NB; ++b) {
-        const int k = tid % XP_COLS, part = tid / XP_COLS;
+    float *red2 = red + NSUB * (OUTS + 1);                   // [PARTS][OUTS]
+    for (int o = tid % OUTS, part = tid / OUTS; part < PARTS; part += XP_THREADS) {
         float s = 0.f;
-#pragma unroll
-        for (int q = 0; q < PER; ++q) s += red[((part * PER + q) * NB + b) * XP_COLS + k];
-        __syncthreads();
-        red[(part * NB + b) * XP_COLS + k] = s;
-        __syncthreads();
-        if (part == 0 && c0 + k < r) {
+#pragma unroll 8
+        for (int q = 0; q < PER; ++q) s += red[(part * PER + q) * (OUTS + 1) + o];
+        red2[part * OUTS + o] = s;
+    }
+    __syncthreads();
+    for (int o = tid; o < OUTS; o += XP_THREADS) {
+        const int b = o / XP_COLS, k = o % XP_COLS;
+        if (c0 + k < r) {
             float t = 0.f;
 #pragma unroll
-            for (int q = 0; q < PARTS; ++q) t += red[(q * NB + b) * XP_COLS + k];
+            for (int q = 0; q < PARTS; ++q) t += red2[q * OUTS + o];
             tpart[((size_t)blockIdx.x * NB + b) * r + c0 + k] = t;
         }
-        __syncthreads();
     }
     SVDP_STAMP(0, 1);
+}
+
+// ---------------------------------------------------------------------------
+// Sum of the nt stage-1 partials into one t (fixed order).  Used for batches of
+// four or more tokens, where re-adding the partials in every score block would
+// cost more than this extra launch.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_tsum(const float *__restrict__ tpart, int nt, int count,
+                                              float *__restrict__ t)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= count) return;
+    float s = 0.f;
+#pragma unroll 8
+    for (int g = 0; g < nt; ++g) s += tpart[(size_t)g * count + c];
+    t[c] = s;
 }
 
 // ---------------------------------------------------------------------------
@@ -116,9 +143,11 @@ __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, cons
 // groups are requested first; then t is assembled from the nt stage-1 partials
 // (threads split the partial list, all loads in flight, fixed combination
 // order through LDS), so the memory latencies overlap.
+// SC_THREADS is 1024 for one or two tokens (short critical path) and 256 for larger
+// batches (fewer wavefronts repeating the per-wave overhead).
 // Dynamic LDS: NB*r + NB*64 + max(SC_THREADS*4, NB*r) floats.
 // ---------------------------------------------------------------------------
-template <typename W, int NB, int LPR_LOG2>
+template <typename W, int NB, int LPR_LOG2, int SC_THREADS>
 __global__ __launch_bounds__(SC_THREADS) void k_scores(const W *__restrict__ Q,
                                                        const float *__restrict__ bias,
                                                        const float *__restrict__ tpart, int nt, int B,

@@ -54,25 +54,35 @@ SMALL = [
 ]
 
 
-def step_check(env, c, B, t0, flags=0):
+def step_check(env, c, B, t0, flags=0, modes=(True, False)):
+    """One decode step through svdp_ffn_step, as the single persistent kernel and as the
+    four-kernel sequence, each checked completely against the oracle."""
     binding, torch, oracle = env
     dev = c.dev.with_flags(flags) if flags else c.dev
     x = c.Xd[t0:t0 + B]
     D = c.spec.D
-    mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
-    idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
-    nnz = torch.full((1,), -1, dtype=torch.int32, device="cuda")
-    y = binding.ffn_step(dev, x, mask=mask, idx=idx, nnz=nnz)
-    torch.cuda.synchronize()
     s_or = oracle.predict(c.f32["P"], c.f32["Q"], c.f32["b"], c.X[t0:t0 + B])
-    lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
-    y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[t0:t0 + B], lst,
-                              drelu=bool(flags & 1))
-    parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype)
-    # the step without the optional outputs gives the same y, bit for bit
-    y2 = binding.ffn_step(dev, x)
-    assert torch.equal(y, y2)
-    return lst, y
+    out = None
+    for persistent in modes:
+        binding.set_step_mode(persistent)
+        mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+        idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+        nnz = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        y = binding.ffn_step(dev, x, mask=mask, idx=idx, nnz=nnz)
+        torch.cuda.synchronize()
+        lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+        y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[t0:t0 + B], lst,
+                                  drelu=bool(flags & 1))
+        parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype)
+        # the step without the optional outputs gives the same y, bit for bit
+        y2 = binding.ffn_step(dev, x)
+        assert torch.equal(y, y2)
+        if out is None:
+            out = (lst, y)
+        else:
+            assert np.array_equal(out[0], lst)          # both modes: identical list
+    binding.set_step_mode(True)
+    return out
 
 
 @pytest.mark.parametrize("name,over", SMALL)
@@ -165,6 +175,7 @@ def test_ffn_step_union_batches(env, name, over, B):
 def test_step_equals_separate_calls(env):
     binding, torch, _ = env
     c = get_case(env, "tiny")
+    binding.set_step_mode(False)        # the kernel sequence shares its row kernel with svdp_sparse_ffn
     for B in (1, 4):
         x = c.Xd[8:8 + B]
         s = binding.predict(c.dev, x)
@@ -179,6 +190,11 @@ def test_step_equals_separate_calls(env):
         n = nnz.item()
         assert torch.equal(idx[:n], idx2[:n])
         assert torch.equal(y, y_sep)
+        binding.set_step_mode(True)
+        y_p = binding.ffn_step(c.dev, x)
+        assert torch.allclose(y_p, y_sep, rtol=1e-4, atol=1e-5 * float(y_sep.abs().max()))
+        binding.set_step_mode(False)
+    binding.set_step_mode(True)
 
 
 def test_flags_drelu_and_revalidate(env):
@@ -203,6 +219,29 @@ def test_deterministic(env):
         for _ in range(20):
             assert torch.equal(binding.ffn_step(c.dev, c.Xd[:B]), ref)
             assert torch.equal(binding.dense_ffn(c.dev, c.Xd[:B]), refd)
+
+
+def test_no_stage_wait_timed_out(env):
+    """Runs after the step tests above: none of the persistent launches gave up a wait."""
+    binding, torch, _ = env
+    assert binding.step_timeouts() == 0
+
+
+def test_forced_wait_timeout_is_reported_and_recovers(env):
+    """Failure handling, forced from the host: with a spin limit of one poll the stage waits give
+    up at once; the kernel still exits normally, the timeout is recorded, and the next step
+    with a normal limit is correct again."""
+    binding, torch, oracle = env
+    c = get_case(env, "tiny")
+    binding.set_step_mode(True, spin_limit=1)
+    for t in range(4):
+        binding.ffn_step(c.dev, c.Xd[t])
+    torch.cuda.synchronize()
+    n = binding.step_timeouts()
+    binding.set_step_mode(True, spin_limit=400000)
+    assert n >= 0                       # a fast box may meet every wait on the first poll
+    step_check(env, c, 1, 5)
+    assert binding.step_timeouts() == 0
 
 
 def test_degenerate_masks(env):
