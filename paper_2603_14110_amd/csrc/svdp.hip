@@ -8,6 +8,7 @@
 #include "svdp_fused.h"
 
 #include <atomic>
+#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -16,7 +17,8 @@ namespace {
 using namespace svdp;
 
 constexpr int XP_MAX_BLOCKS = 128;    // stage-1 row slabs of P (d <= 16384)
-constexpr int ROWS_GRID = 512;        // k_rows blocks (chunks of the row list)
+constexpr int ROWS_GRID = 512;        // most k_rows blocks the workspace holds partial y's for
+constexpr int ROWS_BLOCKS = 256;      // k_rows blocks launched (one chunk of the row list each; measured best)
 constexpr size_t ALIGN = 256;
 
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
@@ -159,7 +161,9 @@ svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_
                         hipStream_t st)
 {
     const int d = L->d, D = L->D;
-    const int grid = NB >= 4 ? ROWS_GRID / 2 : ROWS_GRID;     // big batches: halve the partial-y traffic
+    static const int grid_env = getenv("SVDP_ROWS_GRID") ? atoi(getenv("SVDP_ROWS_GRID")) : 0;
+    int grid = ROWS_BLOCKS;
+    if (grid_env > 0 && grid_env <= ROWS_GRID) grid = grid_env;
     const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
     const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
     static int granted = 64 * 1024;

@@ -17,8 +17,8 @@ constexpr int ROWS_THREADS = 512;    // k_rows block
 constexpr int ROWS_WAVES = ROWS_THREADS / 64;
 constexpr int ROWS_UB = 4;           // k_rows: rows of W_downT fetched together (chunk padded to this)
 constexpr int SCAN_THREADS = 1024;   // k_compact_scan block
-constexpr int RED_COLS = 4;          // k_reduce_y: float4 columns per block
-constexpr int RED_SEGS = 256;        // k_reduce_y: segments of the partial list per block (a power of 4)
+constexpr int RED_COLS = 8;          // k_reduce_y: float4 columns per block (one 128-byte line per partial row)
+constexpr int RED_SEGS = 128;        // k_reduce_y: segments of the partial list per block
 
 // ---------------------------------------------------------------------------
 // Predictor stage 1: partial t = x P over a tile of P   (Sec. 4.1 eq. 2: the
@@ -623,19 +623,23 @@ __global__ __launch_bounds__(RED_COLS *RED_SEGS) void k_reduce_y(const float *__
     }
     red[seg][c] = s;
     __syncthreads();
-    for (int width = RED_SEGS / 4; width >= 1; width /= 4) {
+    for (int cur = RED_SEGS; cur > 1;) {                 // radix-4 tree, fixed order
+        const int next = (cur + 3) / 4;
         float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (seg < width) {
+        if (seg < next) {
             t = red[4 * seg][c];
 #pragma unroll
             for (int q = 1; q < 4; ++q) {
-                const float4 p = red[4 * seg + q][c];
-                t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+                if (4 * seg + q < cur) {
+                    const float4 p = red[4 * seg + q][c];
+                    t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+                }
             }
         }
         __syncthreads();
-        if (seg < width) red[seg][c] = t;
+        if (seg < next) red[seg][c] = t;
         __syncthreads();
+        cur = next;
     }
     if (seg == 0 && v < vpt) reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = red[0][c];
     SVDP_STAMP(3, 1);
