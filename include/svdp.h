@@ -129,19 +129,26 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
                           uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out,
                           void *ws, size_t ws_bytes, void *stream);
 
-/* How svdp_ffn_step runs.  persistent != 0 (the default): one persistent launch,
- * one block per compute unit, whose stages hand their results over through
- * global memory and bounded waits; it needs every block resident at once, so the
- * GPU must not be shared with other work while it runs.  persistent == 0: a
- * sequence of four ordinary launches.  Both give the same mask and index list;
- * y agrees to rounding (the partial sums are cut differently).  Shapes the
- * persistent kernel cannot hold fall back to the sequence by themselves.
- * spin_limit > 0 sets the number of polls after which a stage wait gives up
- * (the step then finishes with undefined output and the timeout is recorded).
- * Process-wide; call it while no step is in flight.                             */
-void svdp_set_step_mode(int32_t persistent, int32_t spin_limit);
+/* How the launches are organised (process-wide; call it while nothing is in flight).
+ *  SVDP_STEP_SEQUENCE      (default) ordinary launches only: svdp_ffn_step is four kernels
+ *                          (x P tiles, scores and mask words, rows -> partial y, sum of the
+ *                          partials); svdp_sparse_ffn / svdp_dense_ffn are the last two.
+ *  SVDP_STEP_MERGED_REDUCE as above, but the row kernel also sums the partial y's: its
+ *                          blocks hand them over through global memory and a bounded wait
+ *                          instead of a kernel boundary.
+ *  SVDP_STEP_PERSISTENT    svdp_ffn_step as ONE persistent launch, one block per compute unit,
+ *                          all four stages handed over that way.
+ * The last two were measured slower than the sequence on MI355X (a kernel boundary is the
+ * cheapest chip-wide hand-over there) and are kept as options.  They need every block of the
+ * launch resident at once, so the GPU must not be shared with other work while they run;
+ * shapes or devices that cannot guarantee it fall back to SVDP_STEP_SEQUENCE by themselves.
+ * All modes give the same mask and index list; y agrees to rounding (partial sums are cut
+ * differently).  spin_limit > 0 sets the number of polls after which a wait gives up (the
+ * call then finishes with undefined output and the timeout is recorded).                    */
+typedef enum { SVDP_STEP_SEQUENCE = 0, SVDP_STEP_PERSISTENT = 1, SVDP_STEP_MERGED_REDUCE = 2 } svdp_step_mode;
+void svdp_set_step_mode(int32_t mode, int32_t spin_limit);
 
-/* Number of workspaces on which a persistent step gave up waiting since the last
+/* Number of workspaces on which a launch gave up waiting since the last
  * call; clears the record.  Synchronises the device: not for use under capture. */
 svdp_status svdp_step_timeouts(int32_t *count);
 

@@ -225,8 +225,11 @@ def stack_glue(x: torch.Tensor, y: torch.Tensor, shift: torch.Tensor, eps: float
     return out
 
 
-def set_step_mode(persistent: bool, spin_limit: int = 0) -> None:
-    lib().svdp_set_step_mode(1 if persistent else 0, int(spin_limit))
+STEP_SEQUENCE, STEP_PERSISTENT, STEP_MERGED_REDUCE = 0, 1, 2
+
+
+def set_step_mode(mode: int, spin_limit: int = 0) -> None:
+    lib().svdp_set_step_mode(int(mode), int(spin_limit))
 
 
 def step_timeouts() -> int:

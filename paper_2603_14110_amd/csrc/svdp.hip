@@ -109,6 +109,49 @@ inline svdp_status hip_status(hipError_t e)
     return e == hipSuccess ? SVDP_OK : SVDP_ERR_HIP;
 }
 
+// ---- control blocks for launches whose blocks hand results to each other ----
+// Control blocks live in static device memory (zero at load, zero again after every
+// launch); one slot per workspace address seen by this process.
+__device__ __align__(256) uint32_t g_step_ctrl[CTRL_SLOTS * CTRL_WORDS];
+
+std::atomic<int> g_fused_mode{0};            // svdp_step_mode
+std::atomic<int> g_spin_limit{400000};       // polls before a stage wait gives up
+std::mutex g_slot_mutex;
+std::vector<const void *> g_slots;
+uint32_t *g_ctrl_base = nullptr;
+int g_num_cus = 0;
+
+bool fused_setup()
+{
+    if (g_ctrl_base != nullptr) return true;
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_step_ctrl)) != hipSuccess || p == nullptr) {
+        (void)hipGetLastError();
+        return false;
+    }
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        return false;
+    }
+    g_num_cus = cus;
+    g_ctrl_base = static_cast<uint32_t *>(p);
+    return true;
+}
+
+// control block of a workspace, or nullptr when none is free
+uint32_t *ctrl_for(const void *ws)
+{
+    std::lock_guard<std::mutex> lock(g_slot_mutex);
+    if (!fused_setup()) return nullptr;
+    for (size_t i = 0; i < g_slots.size(); ++i)
+        if (g_slots[i] == ws) return g_ctrl_base + i * CTRL_WORDS;
+    if (g_slots.size() >= (size_t)CTRL_SLOTS) return nullptr;
+    g_slots.push_back(ws);
+    return g_ctrl_base + (g_slots.size() - 1) * CTRL_WORDS;
+}
+
 // ---- launch helpers, one per kernel, templated on storage type and batch capacity ----
 
 template <typename W, int NB>
@@ -157,21 +200,48 @@ svdp_status launch_scores(const svdp_layer *L, const float *tpart, int nt, int B
 
 template <typename W, int NB, int MODE>
 svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
-                        const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, float *y,
-                        hipStream_t st)
+                        const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base,
+                        float *y, hipStream_t st)
 {
     const int d = L->d, D = L->D;
     static const int grid_env = getenv("SVDP_ROWS_GRID") ? atoi(getenv("SVDP_ROWS_GRID")) : 0;
     int grid = ROWS_BLOCKS;
     if (grid_env > 0 && grid_env <= ROWS_GRID) grid = grid_env;
     const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
-    const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
+    size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
+    const size_t lds_tail = (size_t)ROWS_THREADS * 16;          // the in-launch reduction's tree
+    const W *Wg = static_cast<const W *>(L->W_gate), *Wu = static_cast<const W *>(L->W_up);
+    const W *Wd = static_cast<const W *>(L->W_downT), *xs = static_cast<const W *>(x);
+
+    // Variant that also finishes y inside the launch (needs every block resident at once).
+    if (g_fused_mode.load() == SVDP_STEP_MERGED_REDUCE) {
+        uint32_t *ctrl = ctrl_for(ws_base);
+        const size_t lds_f = lds > lds_tail ? lds : lds_tail;
+        static int granted_f = 64 * 1024;
+        static int resident = -1;
+        if (ctrl != nullptr && allow_lds(k_rows<W, NB, MODE, true>, lds_f, &granted_f) == hipSuccess) {
+            if (resident < 0) {
+                int nb = 0;
+                if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_rows<W, NB, MODE, true>, ROWS_THREADS,
+                                                                 160 * 1024 / 2) != hipSuccess) {
+                    (void)hipGetLastError();
+                    nb = 0;
+                }
+                resident = nb;      // with half the LDS of a CU per block: a lower bound for smaller requests
+            }
+            const bool fits = lds_f <= 160 * 1024 / 2 ? resident * g_num_cus >= grid : g_num_cus >= grid;
+            if (fits && lds_f <= 160 * 1024) {
+                hipLaunchKernelGGL((k_rows<W, NB, MODE, true>), dim3(grid), dim3(ROWS_THREADS), lds_f, st, Wg, Wu, Wd,
+                                   xs, B, d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags,
+                                   w.ypart, y, ctrl, g_spin_limit.load());
+                return hip_status(hipSuccess);
+            }
+        }
+    }
     static int granted = 64 * 1024;
-    if (allow_lds(k_rows<W, NB, MODE>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_rows<W, NB, MODE>), dim3(grid), dim3(ROWS_THREADS), lds, st,
-                       static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
-                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, mask, idx_in, nnz_in,
-                       idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart);
+    if (allow_lds(k_rows<W, NB, MODE, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_rows<W, NB, MODE, false>), dim3(grid), dim3(ROWS_THREADS), lds, st, Wg, Wu, Wd, xs, B, d, D,
+                       mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart, y, nullptr, 0);
     svdp_status s = hip_status(hipSuccess);
     if (s != SVDP_OK) return s;
     const int vpt = d / 4;
@@ -185,49 +255,6 @@ svdp_status launch_compact(const uint64_t *mask, int D, int32_t *idx, int32_t *n
 {
     hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(SCAN_THREADS), 0, st, mask, D / 64, idx, nnz);
     return hip_status(hipSuccess);
-}
-
-// ---- the single persistent kernel ----
-// Control blocks live in static device memory (zero at load, zero again after every
-// launch); one slot per workspace address seen by this process.
-__device__ __align__(256) uint32_t g_step_ctrl[CTRL_SLOTS * CTRL_WORDS];
-
-std::atomic<int> g_fused_mode{0};            // 1: persistent kernel when supported, 0: kernel sequence
-std::atomic<int> g_spin_limit{400000};       // polls before a stage wait gives up
-std::mutex g_slot_mutex;
-std::vector<const void *> g_slots;
-uint32_t *g_ctrl_base = nullptr;
-int g_num_cus = 0;
-
-bool fused_setup()
-{
-    if (g_ctrl_base != nullptr) return true;
-    void *p = nullptr;
-    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_step_ctrl)) != hipSuccess || p == nullptr) {
-        (void)hipGetLastError();
-        return false;
-    }
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
-        (void)hipGetLastError();
-        return false;
-    }
-    g_num_cus = cus;
-    g_ctrl_base = static_cast<uint32_t *>(p);
-    return true;
-}
-
-// control block of a workspace, or nullptr when none is free
-uint32_t *ctrl_for(const void *ws)
-{
-    std::lock_guard<std::mutex> lock(g_slot_mutex);
-    if (!fused_setup()) return nullptr;
-    for (size_t i = 0; i < g_slots.size(); ++i)
-        if (g_slots[i] == ws) return g_ctrl_base + i * CTRL_WORDS;
-    if (g_slots.size() >= (size_t)CTRL_SLOTS) return nullptr;
-    g_slots.push_back(ws);
-    return g_ctrl_base + (g_slots.size() - 1) * CTRL_WORDS;
 }
 
 inline int fused_max_chunk(int D, int G) { return ((D + G - 1) / G + ROWS_UB - 1) / ROWS_UB * ROWS_UB; }
@@ -328,14 +355,14 @@ template <typename W, int NB>
 svdp_status run_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
                      int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
 {
-    if (g_fused_mode.load() != 0) {
+    if (g_fused_mode.load() == SVDP_STEP_PERSISTENT) {
         const svdp_status f = run_step_fused<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st);
         if (f != SVDP_ERR_UNSUPPORTED) return f;
     }
     uint64_t *mask = mask_out ? mask_out : w.mask;
     svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st);
     if (e != SVDP_OK) return e;
-    return launch_rows<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, idx_out, nnz_out, w, y, st);
+    return launch_rows<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, idx_out, nnz_out, w, ws_base, y, st);
 }
 
 svdp_status dispatch_predict(const svdp_layer *L, const void *x, int B, float *s, const Workspace &w, hipStream_t st)
@@ -343,13 +370,16 @@ svdp_status dispatch_predict(const svdp_layer *L, const void *x, int B, float *s
     SVDP_DISPATCH(L->wdtype, nb_of(B), (run_predict<W, NB>(L, x, B, s, nullptr, w, st)));
 }
 svdp_status dispatch_sparse(const svdp_layer *L, const void *x, int B, const int32_t *idx, const int32_t *nnz,
-                            float *y, const Workspace &w, hipStream_t st)
+                            float *y, const Workspace &w, void *ws_base, hipStream_t st)
 {
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, ROWS_LIST>(L, x, B, nullptr, idx, nnz, nullptr, nullptr, w, y, st)));
+    SVDP_DISPATCH(L->wdtype, nb_of(B),
+                  (launch_rows<W, NB, ROWS_LIST>(L, x, B, nullptr, idx, nnz, nullptr, nullptr, w, ws_base, y, st)));
 }
-svdp_status dispatch_dense(const svdp_layer *L, const void *x, int B, float *y, const Workspace &w, hipStream_t st)
+svdp_status dispatch_dense(const svdp_layer *L, const void *x, int B, float *y, const Workspace &w, void *ws_base,
+                           hipStream_t st)
 {
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows<W, NB, ROWS_DENSE>(L, x, B, nullptr, nullptr, nullptr, nullptr, nullptr, w, y, st)));
+    SVDP_DISPATCH(L->wdtype, nb_of(B),
+                  (launch_rows<W, NB, ROWS_DENSE>(L, x, B, nullptr, nullptr, nullptr, nullptr, nullptr, w, ws_base, y, st)));
 }
 svdp_status dispatch_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out,
                           int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
@@ -405,7 +435,7 @@ svdp_status svdp_sparse_ffn(const svdp_layer *layer, const void *x, int32_t B, c
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_sparse(layer, x, B, idx, nnz, y, w, static_cast<hipStream_t>(stream));
+    return dispatch_sparse(layer, x, B, idx, nnz, y, w, ws, static_cast<hipStream_t>(stream));
 }
 
 svdp_status svdp_dense_ffn(const svdp_layer *layer, const void *x, int32_t B, float *y, void *ws, size_t ws_bytes,
@@ -417,7 +447,7 @@ svdp_status svdp_dense_ffn(const svdp_layer *layer, const void *x, int32_t B, fl
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_dense(layer, x, B, y, w, static_cast<hipStream_t>(stream));
+    return dispatch_dense(layer, x, B, y, w, ws, static_cast<hipStream_t>(stream));
 }
 
 svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, float *y, uint64_t *mask_out,
@@ -462,9 +492,9 @@ const char *svdp_status_string(svdp_status st)
 
 const char *svdp_version(void) { return "0.2"; }
 
-void svdp_set_step_mode(int32_t persistent, int32_t spin_limit)
+void svdp_set_step_mode(int32_t mode, int32_t spin_limit)
 {
-    g_fused_mode.store(persistent != 0 ? 1 : 0);
+    if (mode >= SVDP_STEP_SEQUENCE && mode <= SVDP_STEP_MERGED_REDUCE) g_fused_mode.store(mode);
     if (spin_limit > 0) g_spin_limit.store(spin_limit);
 }
 

@@ -6,6 +6,7 @@
 #pragma once
 
 #include "svdp_device.h"
+#include "svdp_sync.h"
 
 namespace svdp {
 
@@ -349,12 +350,13 @@ enum RowsMode { ROWS_DENSE = 0, ROWS_LIST = 1, ROWS_MASK = 2 };
 
 __device__ __forceinline__ int chunk_of(int n, int G) { return (n + G - 1) / G; }
 
-template <typename W, int NB, int MODE>
+template <typename W, int NB, int MODE, bool FINISH>
 __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4))) void k_rows(
     const W *__restrict__ Wg, const W *__restrict__ Wu, const W *__restrict__ WdT, const W *__restrict__ x, int B,
     int d, int D, const uint64_t *__restrict__ mask, const int32_t *__restrict__ idx_in,
     const int32_t *__restrict__ nnz_in, int32_t *__restrict__ idx_out, int32_t *__restrict__ nnz_out,
-    int32_t *__restrict__ n_used, int max_chunk, uint32_t flags, float *__restrict__ ypart)
+    int32_t *__restrict__ n_used, int max_chunk, uint32_t flags, float *ypart, float *__restrict__ y,
+    uint32_t *ctrl, int spin_limit)
 {
     constexpr int VEC = Elem<W>::VEC;
     constexpr int UA = NB <= 2 ? 8 : 4;     // 16-byte loads in flight per matrix in phase A
@@ -402,11 +404,12 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
     const int hi = min(n, lo + chunk);
     const int cnt = hi - lo;
     if (blockIdx.x == 0 && tid == 0) {
-        if (MODE != ROWS_DENSE) *n_used = n;
+        if (MODE != ROWS_DENSE && !FINISH) *n_used = n;
         if (MODE == ROWS_MASK && nnz_out != nullptr) *nnz_out = n;
     }
-    if (cnt <= 0) return;
+    if (!FINISH && cnt <= 0) return;
 
+    if (cnt > 0) {
     // Phase B walks the chunk in groups of UB rows; the last group is padded with
     // repeats of the last row whose h is 0, so no loop below needs a tail.
     const int ngroups = (cnt + UB - 1) / UB;
@@ -575,14 +578,91 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
         }
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            float4 *out = reinterpret_cast<float4 *>(ypart + ((size_t)blockIdx.x * NB + b) * d + (size_t)v * VEC);
+            float *outf = ypart + ((size_t)blockIdx.x * NB + b) * d + (size_t)v * VEC;
+            if (FINISH) {
+                // other blocks of this launch read it: written through to memory
 #pragma unroll
-            for (int e4 = 0; e4 < VEC / 4; ++e4)
-                out[e4] = make_float4(acc[b][4 * e4], acc[b][4 * e4 + 1], acc[b][4 * e4 + 2], acc[b][4 * e4 + 3]);
+                for (int e4 = 0; e4 < VEC / 4; ++e4)
+                    store_wt16(outf + 4 * e4, acc[b][4 * e4], acc[b][4 * e4 + 1], acc[b][4 * e4 + 2], acc[b][4 * e4 + 3]);
+            } else {
+                float4 *out = reinterpret_cast<float4 *>(outf);
+#pragma unroll
+                for (int e4 = 0; e4 < VEC / 4; ++e4)
+                    out[e4] = make_float4(acc[b][4 * e4], acc[b][4 * e4 + 1], acc[b][4 * e4 + 2], acc[b][4 * e4 + 3]);
+            }
         }
     }
+    }   // cnt > 0
     SVDP_STAMP(2, 5);
     SVDP_STAMP_CLK(2, 7);
+    if (!FINISH) return;
+
+    // ---- second stage of the down-projection reduction inside the same launch:
+    // y[b][cols] = sum over the blocks that had rows, for 128-byte column slices ----
+    wait_stores_done();
+    __syncthreads();
+    if (tid == 0) signal(ctrl, CTRL_Y, blockIdx.x);
+    wait_stage(ctrl, CTRL_Y, G, spin_limit);
+    {
+        constexpr int RC = 8, RS = ROWS_THREADS / RC;               // float4 columns x segments of partials
+        float4 *red = reinterpret_cast<float4 *>(smem16);           // [RS][RC]
+        const int gact = n > 0 ? (n + chunk - 1) / chunk : 0;
+        const int vpt = d / 4;
+        const int c = tid % RC, seg = tid / RC;
+        for (int cb = blockIdx.x; cb * RC < vpt; cb += G) {
+            const int v = cb * RC + c;
+            for (int b = 0; b < B; ++b) {
+                float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (v < vpt) {
+                    // the (at most G/RS = 4 per pass) partials of this thread, fetched together
+                    for (int g0 = seg; g0 < gact; g0 += 4 * RS) {
+                        const float *base = ypart + (size_t)b * d + (size_t)v * 4;
+                        const size_t gs = (size_t)NB * d;
+                        const int g1 = g0 + RS, g2 = g0 + 2 * RS, g3 = g0 + 3 * RS;
+                        f32x4_t p0, p1, p2, p3;
+                        load_wt16x4(base + g0 * gs, base + (g1 < gact ? g1 : g0) * gs, base + (g2 < gact ? g2 : g0) * gs,
+                                    base + (g3 < gact ? g3 : g0) * gs, p0, p1, p2, p3);
+                        s.x += p0.x; s.y += p0.y; s.z += p0.z; s.w += p0.w;
+                        if (g1 < gact) { s.x += p1.x; s.y += p1.y; s.z += p1.z; s.w += p1.w; }
+                        if (g2 < gact) { s.x += p2.x; s.y += p2.y; s.z += p2.z; s.w += p2.w; }
+                        if (g3 < gact) { s.x += p3.x; s.y += p3.y; s.z += p3.z; s.w += p3.w; }
+                    }
+                }
+                __syncthreads();
+                red[seg * RC + c] = s;
+                __syncthreads();
+                for (int cur = RS; cur > 1;) {                      // radix-4 tree, fixed order
+                    const int next = (cur + 3) / 4;
+                    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (seg < next) {
+                        t = red[(4 * seg) * RC + c];
+#pragma unroll
+                        for (int q = 1; q < 4; ++q) {
+                            if (4 * seg + q < cur) {
+                                const float4 p = red[(4 * seg + q) * RC + c];
+                                t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+                            }
+                        }
+                    }
+                    __syncthreads();
+                    if (seg < next) red[seg * RC + c] = t;
+                    __syncthreads();
+                    cur = next;
+                }
+                if (seg == 0 && v < vpt) reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = red[c];
+            }
+        }
+    }
+    // the last block to leave zeroes the counters for the next launch
+    if (tid == 0) {
+        wait_stores_done();
+        const uint32_t old = __hip_atomic_fetch_add(ctrl + CTRL_EXIT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == (uint32_t)G - 1u) {
+            for (int q = 0; q < CTRL_GROUPS; ++q)
+                __hip_atomic_store(ctrl + CTRL_Y + q * CTRL_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(ctrl + CTRL_EXIT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------

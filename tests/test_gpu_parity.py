@@ -54,17 +54,17 @@ SMALL = [
 ]
 
 
-def step_check(env, c, B, t0, flags=0, modes=(True, False)):
-    """One decode step through svdp_ffn_step, as the single persistent kernel and as the
-    four-kernel sequence, each checked completely against the oracle."""
+def step_check(env, c, B, t0, flags=0, modes=(0, 2, 1)):
+    """One decode step through svdp_ffn_step in every launch organisation (merged reduction,
+    single persistent kernel, plain four-kernel sequence), each checked completely against the oracle."""
     binding, torch, oracle = env
     dev = c.dev.with_flags(flags) if flags else c.dev
     x = c.Xd[t0:t0 + B]
     D = c.spec.D
     s_or = oracle.predict(c.f32["P"], c.f32["Q"], c.f32["b"], c.X[t0:t0 + B])
     out = None
-    for persistent in modes:
-        binding.set_step_mode(persistent)
+    for mode in modes:
+        binding.set_step_mode(mode)
         mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
         idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
         nnz = torch.full((1,), -1, dtype=torch.int32, device="cuda")
@@ -81,7 +81,7 @@ def step_check(env, c, B, t0, flags=0, modes=(True, False)):
             out = (lst, y)
         else:
             assert np.array_equal(out[0], lst)          # both modes: identical list
-    binding.set_step_mode(True)
+    binding.set_step_mode(binding.STEP_SEQUENCE)
     return out
 
 
@@ -133,11 +133,14 @@ def test_sparse_ffn_arbitrary_lists(env, name, over):
             idx = torch.zeros(D, dtype=torch.int32, device="cuda")
             idx[: lst.size] = torch.from_numpy(lst).cuda()
             nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
-            y = binding.sparse_ffn(c.dev, c.Xd[:B], idx, nnz).cpu().numpy()
             y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B], lst)
-            parity.check_y(y, y_ref, c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, c.X[:B], lst))
-            if lst.size == 0:
-                assert not y.any()
+            slack = parity.fp32_forward_bound(c.f32, c.X[:B], lst)
+            for mode in (binding.STEP_MERGED_REDUCE, binding.STEP_SEQUENCE):
+                binding.set_step_mode(mode)
+                y = binding.sparse_ffn(c.dev, c.Xd[:B], idx, nnz).cpu().numpy()
+                parity.check_y(y, y_ref, c.spec.dtype, slack=slack)
+                if lst.size == 0:
+                    assert not y.any()
 
 
 @pytest.mark.parametrize("name,over", SMALL)
@@ -145,9 +148,11 @@ def test_dense_ffn(env, name, over):
     binding, torch, oracle = env
     c = get_case(env, name, **over)
     for B in (1, 4, 7):
-        y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
         y_ref = oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B])
-        parity.check_y(y, y_ref, c.spec.dtype)
+        for mode in (binding.STEP_MERGED_REDUCE, binding.STEP_SEQUENCE):
+            binding.set_step_mode(mode)
+            y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
+            parity.check_y(y, y_ref, c.spec.dtype)
     yd = binding.dense_ffn(c.dev.with_flags(binding.FLAG_DRELU), c.Xd[:2]).cpu().numpy()
     parity.check_y(yd, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:2], drelu=True),
                    c.spec.dtype)
@@ -175,7 +180,7 @@ def test_ffn_step_union_batches(env, name, over, B):
 def test_step_equals_separate_calls(env):
     binding, torch, _ = env
     c = get_case(env, "tiny")
-    binding.set_step_mode(False)        # the kernel sequence shares its row kernel with svdp_sparse_ffn
+    binding.set_step_mode(binding.STEP_SEQUENCE)   # the kernel sequence shares its row kernel with svdp_sparse_ffn
     for B in (1, 4):
         x = c.Xd[8:8 + B]
         s = binding.predict(c.dev, x)
@@ -190,11 +195,11 @@ def test_step_equals_separate_calls(env):
         n = nnz.item()
         assert torch.equal(idx[:n], idx2[:n])
         assert torch.equal(y, y_sep)
-        binding.set_step_mode(True)
-        y_p = binding.ffn_step(c.dev, x)
-        assert torch.allclose(y_p, y_sep, rtol=1e-4, atol=1e-5 * float(y_sep.abs().max()))
-        binding.set_step_mode(False)
-    binding.set_step_mode(True)
+        for mode in (binding.STEP_PERSISTENT, binding.STEP_MERGED_REDUCE):
+            binding.set_step_mode(mode)
+            y_p = binding.ffn_step(c.dev, x)
+            assert torch.allclose(y_p, y_sep, rtol=1e-4, atol=1e-5 * float(y_sep.abs().max()))
+        binding.set_step_mode(binding.STEP_SEQUENCE)
 
 
 def test_flags_drelu_and_revalidate(env):
@@ -233,12 +238,13 @@ def test_forced_wait_timeout_is_reported_and_recovers(env):
     with a normal limit is correct again."""
     binding, torch, oracle = env
     c = get_case(env, "tiny")
-    binding.set_step_mode(True, spin_limit=1)
-    for t in range(4):
-        binding.ffn_step(c.dev, c.Xd[t])
-    torch.cuda.synchronize()
+    for mode in (binding.STEP_PERSISTENT, binding.STEP_MERGED_REDUCE):
+        binding.set_step_mode(mode, spin_limit=1)
+        for t in range(4):
+            binding.ffn_step(c.dev, c.Xd[t])
+        torch.cuda.synchronize()
     n = binding.step_timeouts()
-    binding.set_step_mode(True, spin_limit=400000)
+    binding.set_step_mode(binding.STEP_SEQUENCE, spin_limit=400000)
     assert n >= 0                       # a fast box may meet every wait on the first poll
     step_check(env, c, 1, 5)
     assert binding.step_timeouts() == 0
