@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--table4", action="store_true",
+                    help="instead of the step benchmark: FFN-only speed-up at fixed sparsity on the paper's three shapes")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
@@ -191,6 +193,61 @@ def run_stack(a, torch, np, binding, cost, synth):
     return res
 
 
+def measured_traffic(a):
+    """HBM bytes per step from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs,
+    calibrated on a plain copy), for the workload that summary covers; None otherwise."""
+    if not (a.workload == "7b" and a.batch == 1 and a.rank in (0, 256) and a.flags == 0):
+        return None
+    path = os.path.join(ROOT, "profiles", "ffn_step_7b_pmc_traffic.txt")
+    try:
+        out = {}
+        for line in open(path):
+            if line.startswith("traffic per step"):
+                out["bytes_per_step"] = float(line.split(":")[1].split()[0])
+            elif line.startswith("algorithmic bytes per step"):
+                out["algorithmic_bytes_same_steps"] = float(line.split(":")[1].split()[0])
+        return out if len(out) == 2 else None
+    except OSError:
+        return None
+
+
+def table4(a):
+    """The protocol of the paper's executor table (Sec. 5.4): FFN only, predictor excluded, the same
+    fixed sparsity on all three projections, speed-up over the dense FFN on the same GPU."""
+    import numpy as np
+    import torch
+
+    from paper_2603_14110_amd import binding
+
+    shapes = {"llama2-7b": (4096, 11008), "mistral-7b": (4096, 14336), "qwen2-7b": (3584, 18944)}
+    rows = []
+    rng = np.random.default_rng(7)
+    for name, (d, D) in shapes.items():
+        g = torch.Generator(device="cuda").manual_seed(11)
+        mk = lambda *sh: (torch.randn(*sh, device="cuda", generator=g) / d ** 0.5).to(torch.bfloat16)
+        base = binding.DeviceLayer(mk(d, 64), mk(D, 64), torch.zeros(D, device="cuda"), mk(D, d), mk(D, d), mk(D, d))
+        copies = [base] + [base.clone() for _ in range(7)]
+        K = 64
+        X = torch.randn(K, 1, d, device="cuda", generator=g).to(torch.bfloat16)
+        Y = torch.zeros(K, 1, d, device="cuda")
+        ws = base.workspace(1)
+        ms_dense, _ = time_graph(torch, lambda k: binding.dense_ffn(copies[k % 8], X[k], ws=ws, out=Y[k]), K, 4, 3)
+        for sp in (0.20, 0.50, 0.80, 0.90, 0.95):
+            n = int(round((1.0 - sp) * D))
+            IDX = torch.zeros(K, D, dtype=torch.int32, device="cuda")
+            for k in range(K):
+                IDX[k, :n] = torch.from_numpy(np.sort(rng.choice(D, n, replace=False)).astype(np.int32)).cuda()
+            nnz = torch.tensor([n], dtype=torch.int32, device="cuda")
+            ms, _ = time_graph(torch, lambda k: binding.sparse_ffn(copies[k % 8], X[k], IDX[k], nnz, ws=ws, out=Y[k]),
+                               K, 4, 3)
+            rows.append({"shape": name, "d": d, "D": D, "sparsity": sp, "sparse_us": ms * 1e3 / K,
+                         "dense_us": ms_dense * 1e3 / K, "speedup": ms_dense / ms})
+        del copies, base
+        torch.cuda.empty_cache()
+    print(json.dumps({"table": "FFN-only speed-up vs dense at fixed sparsity, predictor excluded, bf16, batch 1, "
+                               "cold weights (8 copies)", "rows": rows}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -204,6 +261,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     binding.lib()
+    if a.table4:
+        table4(a)
+        return
     r = (run_stack if a.workload == "stack" else run_layer)(a, torch, np, binding, cost, synth)
     if a.calib_copy_mb:
         n = a.calib_copy_mb << 20
@@ -212,6 +272,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
+    tr = measured_traffic(a)
     K, B, Lyr = a.steps, a.batch, r["layers"]
     us_step, us_dense = r["us_step"], r["us_dense"]
     achieved = r["bytes_step"] / (us_step * 1e-6) / 1e9
@@ -245,7 +306,10 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": (tr or {}).get("bytes_per_step"),
+            "traffic_algorithmic_bytes_same_steps": (tr or {}).get("algorithmic_bytes_same_steps"),
+            "traffic_source": "profiles/ffn_step_7b_pmc_traffic.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; 64-token run)"
+                              if tr else None,
             "kernel": "whole step: all kernels svdp_ffn_step launches (k_xP, k_scores, k_rows, k_reduce_y), "
                       "timed together with HIP events around the replayed graph",
             "algorithmic_bytes_per_step": r["bytes_step"],

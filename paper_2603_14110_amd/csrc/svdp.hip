@@ -173,11 +173,10 @@ svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, i
     return hip_status(hipSuccess);
 }
 
-template <typename W, int NB, int LPR_LOG2>
-svdp_status launch_scores_lpr(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
+template <typename W, int NB, int LPR_LOG2, int THREADS>
+svdp_status launch_scores_thr(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
                               uint64_t *mask_out, hipStream_t st)
 {
-    constexpr int THREADS = NB <= 2 ? 1024 : 256;
     const size_t tsp = (size_t)NB * L->r > (size_t)THREADS * 4 ? (size_t)NB * L->r : (size_t)THREADS * 4;
     const size_t lds = ((size_t)NB * L->r + (size_t)NB * SC_SLAB + tsp) * 4;
     static int granted = 64 * 1024;
@@ -185,6 +184,16 @@ svdp_status launch_scores_lpr(const svdp_layer *L, const float *tpart, int nt, i
     hipLaunchKernelGGL((k_scores<W, NB, LPR_LOG2, THREADS>), dim3(L->D / SC_SLAB), dim3(THREADS), lds, st,
                        static_cast<const W *>(L->Q), L->b, tpart, nt, B, L->D, L->r, s_out, mask_out);
     return hip_status(hipSuccess);
+}
+
+template <typename W, int NB, int LPR_LOG2>
+svdp_status launch_scores_lpr(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
+                              uint64_t *mask_out, hipStream_t st)
+{
+    // block size: 512 threads for one or two tokens (short critical path), 256 for larger batches
+    // (fewer wavefronts repeating the per-wave overhead); measured on the 7B and Mistral shapes
+    if (NB <= 2) return launch_scores_thr<W, NB, LPR_LOG2, 512>(L, tpart, nt, B, s_out, mask_out, st);
+    return launch_scores_thr<W, NB, LPR_LOG2, 256>(L, tpart, nt, B, s_out, mask_out, st);
 }
 
 template <typename W, int NB>

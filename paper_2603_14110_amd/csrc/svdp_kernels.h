@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void k_tsum(const float *__restrict__ tpart, i
 // groups are requested first; then t is assembled from the nt stage-1 partials
 // (threads split the partial list, all loads in flight, fixed combination
 // order through LDS), so the memory latencies overlap.
-// SC_THREADS is 1024 for one or two tokens (short critical path) and 256 for larger
+// SC_THREADS is 512 for one or two tokens (short critical path) and 256 for larger
 // batches (fewer wavefronts repeating the per-wave overhead).
 // Dynamic LDS: NB*r + NB*64 + max(SC_THREADS*4, NB*r) floats.
 // ---------------------------------------------------------------------------

@@ -177,6 +177,47 @@ def test_ffn_step_union_batches(env, name, over, B):
         step_check(env, c, B, t0)
 
 
+def test_random_shapes(env):
+    """Seeded random shapes (ragged d and r, any B, both storage types, plain random weights):
+    every entry point against the oracle.  Covers launch-shape arithmetic the named workloads miss."""
+    binding, torch, oracle = env
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        dt = "bf16" if case % 2 else "f32"
+        e = 8 if dt == "bf16" else 4
+        d = int(rng.integers(1, 160)) * e
+        r = int(rng.integers(1, 20)) * e
+        D = int(rng.integers(1, 40)) * 64
+        B = int(rng.integers(1, 9))
+        st = lambda a: synth.to_storage(a, dt)
+        Wg, Wu, Wd = (st(rng.standard_normal((D, d)) / np.sqrt(d)) for _ in range(3))
+        P, Q = st(rng.standard_normal((d, r)) / np.sqrt(d)), st(rng.standard_normal((D, r)))
+        b = (rng.standard_normal(D) * 0.5 - 1.0).astype(np.float32)
+        X = st(rng.standard_normal((B, d)))
+        f = {k: synth.storage_to_f32(v, dt) for k, v in dict(W_gate=Wg, W_up=Wu, W_downT=Wd, P=P, Q=Q).items()}
+        Xf = synth.storage_to_f32(X, dt)
+        dev = binding.DeviceLayer(*(binding.to_device(a, dt) for a in (P, Q)), torch.from_numpy(b).cuda(),
+                                  *(binding.to_device(a, dt) for a in (Wg, Wu, Wd)))
+        Xd = binding.to_device(X, dt)
+        s_or = oracle.predict(f["P"], f["Q"], b, Xf)
+        s = binding.predict(dev, Xd).cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(s - s_or) <= 2e-5 * np.abs(s_or).max(axis=1, keepdims=True)), (case, d, r, D, B, dt)
+        for mode in (binding.STEP_SEQUENCE, binding.STEP_MERGED_REDUCE, binding.STEP_PERSISTENT):
+            binding.set_step_mode(mode)
+            mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+            idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+            nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+            y = binding.ffn_step(dev, Xd, mask=mask, idx=idx, nnz=nnz)
+            lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+            y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], Xf, lst)
+            parity.check_y(y.cpu().numpy(), y_ref, dt, slack=parity.fp32_forward_bound(f, Xf, lst))
+            yd = binding.dense_ffn(dev, Xd).cpu().numpy()
+            parity.check_y(yd, oracle.dense_ffn(f["W_gate"], f["W_up"], f["W_downT"], Xf), dt,
+                           slack=parity.fp32_forward_bound(f, Xf, np.arange(D)))
+        binding.set_step_mode(binding.STEP_SEQUENCE)
+    assert binding.step_timeouts() == 0
+
+
 def test_step_equals_separate_calls(env):
     binding, torch, _ = env
     c = get_case(env, "tiny")
