@@ -129,6 +129,14 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
                           uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out,
                           void *ws, size_t ws_bytes, void *stream);
 
+/* Stage 3 of svdp_ffn_step alone (the dominant kernel, exposed so that it can be timed by
+ * itself): scans the mask words, and for this launch's row blocks computes gate, up and the
+ * partial down projection over the active rows (Alg. 3's three kernels).  The partial y's stay
+ * in the workspace; no y is produced.  mask: device [D/64] words as written by svdp_compact
+ * or svdp_ffn_step.                                                                          */
+svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask,
+                             void *ws, size_t ws_bytes, void *stream);
+
 /* How the launches are organised (process-wide; call it while nothing is in flight).
  *  SVDP_STEP_SEQUENCE      (default) ordinary launches only: svdp_ffn_step is four kernels
  *                          (x P tiles, scores and mask words, rows -> partial y, sum of the

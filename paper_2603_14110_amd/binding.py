@@ -23,7 +23,7 @@ MAX_BATCH = 8
 EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
     "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version", "svdp_set_step_mode",
-    "svdp_step_timeouts",
+    "svdp_step_timeouts", "svdp_active_rows",
 ]
 
 
@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
     L.svdp_dense_ffn.argtypes = [lp, vp, i32, vp, vp, sz, vp]
     L.svdp_ffn_step.argtypes = [lp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     L.svdp_stack_glue.argtypes = [vp, vp, vp, i32, i32, ctypes.c_float, vp, vp]
+    L.svdp_active_rows.argtypes = [lp, vp, i32, vp, vp, sz, vp]
+    L.svdp_active_rows.restype = ctypes.c_int
     for n in ("svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn", "svdp_ffn_step",
               "svdp_stack_glue"):
         getattr(L, n).restype = ctypes.c_int
@@ -213,6 +215,14 @@ def ffn_step(layer: DeviceLayer, x: torch.Tensor, ws: Optional[torch.Tensor] = N
     _check(lib().svdp_ffn_step(ctypes.byref(layer.c), _ptr(x), B, _ptr(y), _ptr(mask), _ptr(idx), _ptr(nnz),
                                _ptr(ws), ws.numel(), _stream()), "svdp_ffn_step")
     return y
+
+
+def active_rows(layer: DeviceLayer, x: torch.Tensor, mask: torch.Tensor, ws: Optional[torch.Tensor] = None) -> None:
+    """Stage 3 of the step alone (partial y's stay in the workspace); for timing the dominant kernel."""
+    x, B = _x2(layer, x)
+    ws = layer.workspace(B) if ws is None else ws
+    _check(lib().svdp_active_rows(ctypes.byref(layer.c), _ptr(x), B, _ptr(mask), _ptr(ws), ws.numel(), _stream()),
+           "svdp_active_rows")
 
 
 def stack_glue(x: torch.Tensor, y: torch.Tensor, shift: torch.Tensor, eps: float = 1e-6,

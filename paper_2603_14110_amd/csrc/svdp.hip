@@ -390,6 +390,27 @@ svdp_status dispatch_dense(const svdp_layer *L, const void *x, int B, float *y, 
     SVDP_DISPATCH(L->wdtype, nb_of(B),
                   (launch_rows<W, NB, ROWS_DENSE>(L, x, B, nullptr, nullptr, nullptr, nullptr, nullptr, w, ws_base, y, st)));
 }
+template <typename W, int NB>
+svdp_status launch_rows_only(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const Workspace &w,
+                             hipStream_t st)
+{
+    const int d = L->d, D = L->D;
+    const int grid = ROWS_BLOCKS;
+    const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
+    const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_rows<W, NB, ROWS_MASK, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_rows<W, NB, ROWS_MASK, false>), dim3(grid), dim3(ROWS_THREADS), lds, st,
+                       static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
+                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, mask, nullptr, nullptr,
+                       nullptr, nullptr, w.nnz, max_chunk, L->flags, w.ypart, nullptr, nullptr, 0);
+    return hip_status(hipSuccess);
+}
+svdp_status dispatch_rows_only(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const Workspace &w,
+                               hipStream_t st)
+{
+    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows_only<W, NB>(L, x, B, mask, w, st)));
+}
 svdp_status dispatch_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out,
                           int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
 {
@@ -469,6 +490,18 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
     return dispatch_step(layer, x, B, y, mask_out, idx_out, nnz_out, w, ws, static_cast<hipStream_t>(stream));
+}
+
+svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask, void *ws,
+                             size_t ws_bytes, void *stream)
+{
+    svdp_status st = check_layer(layer, false, true);
+    if (st != SVDP_OK) return st;
+    if (x == nullptr || mask == nullptr || bad_batch(B) || !aligned16(x)) return SVDP_ERR_INVALID_ARG;
+    Workspace w;
+    st = check_ws(layer, B, ws, ws_bytes, &w);
+    if (st != SVDP_OK) return st;
+    return dispatch_rows_only(layer, x, B, mask, w, static_cast<hipStream_t>(stream));
 }
 
 svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift, int32_t d, int32_t dtype, float eps,

@@ -243,6 +243,28 @@ def test_step_equals_separate_calls(env):
         binding.set_step_mode(binding.STEP_SEQUENCE)
 
 
+def test_active_rows_stage_alone(env):
+    """svdp_active_rows (stage 3 alone, used to time the dominant kernel): the partial y's it
+    leaves in the workspace add up to the step's y."""
+    binding, torch, oracle = env
+    c = get_case(env, "tiny", d=1024, D=2560, r=72, dtype="bf16", seed=7, k_dom=32)
+    for B in (1, 4):
+        x = c.Xd[2:2 + B]
+        D, d = c.spec.D, c.spec.d
+        mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+        nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws = torch.zeros(binding.workspace_bytes(c.dev, B), dtype=torch.uint8, device="cuda")
+        y = binding.ffn_step(c.dev, x, ws=ws, mask=mask, nnz=nnz).clone()
+        ws.zero_()
+        binding.active_rows(c.dev, x, mask, ws=ws)
+        torch.cuda.synchronize()
+        # the partial y's are the last region of the workspace: [512 blocks][NB][d] fp32, unused ones zero here
+        NB = 1 if B == 1 else 4
+        part = ws[-512 * NB * d * 4:].view(torch.float32).view(512, NB, d)[:, :B].double().sum(dim=0)
+        assert torch.allclose(part.float(), y, rtol=1e-4, atol=1e-5 * float(y.abs().max()))
+        assert torch.equal(binding.ffn_step(c.dev, x, ws=ws), y)
+
+
 def test_flags_drelu_and_revalidate(env):
     binding, torch, oracle = env
     c = get_case(env, "tiny", dtype="bf16")
