@@ -668,17 +668,27 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
 // ---------------------------------------------------------------------------
 // y[b][:] = sum over the blocks of k_rows that had work (second stage of the
 // deterministic down-projection reduction, App. C).
-// A block owns RED_COLS float4 columns of one token; the list of partials is
-// cut into RED_SEGS contiguous segments summed by different threads (so all
-// loads are in flight at once) and the segment sums are combined by a
-// radix-4 tree through LDS.  The order depends only on the number of partials.
+// A block owns RED_COLS float4 columns (one 128-byte line) of one token; the list
+// of partials is cut into RED_SEGS contiguous segments summed by different
+// threads (all loads in flight at once); the eight segments of a wave are then
+// combined with lane shifts, the sixteen waves through LDS.  The order depends
+// only on the number of partials.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ float seg8_sum(float v)
+{
+    v += dpp_move<0x128>(v);        // row_ror:8  -> lanes l and l^8
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
 __global__ __launch_bounds__(RED_COLS *RED_SEGS) void k_reduce_y(const float *__restrict__ ypart,
                                                                  const int32_t *__restrict__ n_ptr, int n_fixed,
                                                                  int D, int G, int NB, int B, int d,
                                                                  float *__restrict__ y)
 {
-    __shared__ float4 red[RED_SEGS][RED_COLS];
+    static_assert(RED_COLS == 8, "a wave holds 8 columns x 8 segments");
+    __shared__ float4 wred[RED_COLS * RED_SEGS / 64][RED_COLS];
     SVDP_STAMP(3, 0);
     int n = n_ptr != nullptr ? *n_ptr : n_fixed;
     n = max(0, min(n, D));
@@ -701,27 +711,19 @@ __global__ __launch_bounds__(RED_COLS *RED_SEGS) void k_reduce_y(const float *__
             s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
         }
     }
-    red[seg][c] = s;
+    s.x = seg8_sum(s.x); s.y = seg8_sum(s.y); s.z = seg8_sum(s.z); s.w = seg8_sum(s.w);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane < RED_COLS) wred[wave][lane] = s;
     __syncthreads();
-    for (int cur = RED_SEGS; cur > 1;) {                 // radix-4 tree, fixed order
-        const int next = (cur + 3) / 4;
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (seg < next) {
-            t = red[4 * seg][c];
+    if (threadIdx.x < RED_COLS && v < vpt) {
+        float4 t = wred[0][c];
 #pragma unroll
-            for (int q = 1; q < 4; ++q) {
-                if (4 * seg + q < cur) {
-                    const float4 p = red[4 * seg + q][c];
-                    t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
-                }
-            }
+        for (int q = 1; q < RED_COLS * RED_SEGS / 64; ++q) {
+            const float4 p = wred[q][c];
+            t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
         }
-        __syncthreads();
-        if (seg < next) red[seg][c] = t;
-        __syncthreads();
-        cur = next;
+        reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = t;
     }
-    if (seg == 0 && v < vpt) reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = red[0][c];
     SVDP_STAMP(3, 1);
 }
 
