@@ -371,11 +371,13 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
     SVDP_STAMP(2, 0);
     SVDP_STAMP_CLK(2, 6);
 
-    // ---- stage x as stored (no conversion); rows of a batch beyond B are zero ----
+    // ---- request x (as stored, no conversion; rows of a batch beyond B are zero).  The first
+    // vector of every token stays in registers until the list is known, so that the request
+    // for the mask words below is in flight together with it ----
+    uint4 xfirst[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b)
-        for (int v = tid; v < nvec; v += ROWS_THREADS)
-            xraw[b * nvec + v] = b < B ? load_raw(x + (size_t)b * d + (size_t)v * VEC) : make_uint4(0u, 0u, 0u, 0u);
+        xfirst[b] = (b < B && tid < nvec) ? load_raw(x + (size_t)b * d + (size_t)tid * VEC) : make_uint4(0u, 0u, 0u, 0u);
 
     // ---- the list: n, this block's chunk [lo, hi) ----
     // ROWS_MASK: every wave scans the popcounts of all mask words by itself (lane l owns
@@ -399,6 +401,12 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
         n = __builtin_amdgcn_readlane(inc, 63);
     }
     SVDP_STAMP(2, 1);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (tid < nvec) xraw[b * nvec + tid] = xfirst[b];
+        for (int v = tid + ROWS_THREADS; v < nvec; v += ROWS_THREADS)
+            xraw[b * nvec + v] = b < B ? load_raw(x + (size_t)b * d + (size_t)v * VEC) : make_uint4(0u, 0u, 0u, 0u);
+    }
     const int chunk = chunk_of(n, G);
     const int lo = min(n, (int)blockIdx.x * chunk);
     const int hi = min(n, lo + chunk);
