@@ -8,7 +8,6 @@
 #include "svdp_fused.h"
 
 #include <atomic>
-#include <cstdlib>
 #include <mutex>
 #include <vector>
 
@@ -17,13 +16,12 @@ namespace {
 using namespace svdp;
 
 constexpr int XP_MAX_BLOCKS = 128;    // stage-1 row slabs of P (d <= 16384)
-constexpr int ROWS_GRID = 512;        // most k_rows blocks the workspace holds partial y's for
-constexpr int ROWS_BLOCKS = 256;      // k_rows blocks launched (one chunk of the row list each; measured best)
+constexpr int ROWS_BLOCKS = 256;      // k_rows blocks: one chunk of the row list and one partial y each (128 to
+                                      // 512 were measured; 256 is best for every batch size)
 constexpr size_t ALIGN = 256;
 
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 inline int nb_of(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : 8; }
-inline int elem_bytes(int dt) { return dt == SVDP_F32 ? 4 : 2; }
 inline int vec_of(int dt) { return dt == SVDP_F32 ? 4 : 8; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -53,11 +51,10 @@ svdp_status check_layer(const svdp_layer *L, bool need_pred, bool need_ffn)
 }
 
 // Workspace layout (all offsets 256-byte aligned):
-//   tpart [XP_MAX_BLOCKS + 1][NB][r] f32 | mask [D/64] u64 | idx [D] i32 | nnz i32 | ypart [ROWS_GRID][NB][d] f32
+//   tpart [XP_MAX_BLOCKS + 1][NB][r] f32 | mask [D/64] u64 | nnz i32 | ypart [ROWS_BLOCKS][NB][d] f32
 struct Workspace {
     float *tpart;
     uint64_t *mask;
-    int32_t *idx;
     int32_t *nnz;
     float *ypart;
     size_t bytes;
@@ -72,12 +69,10 @@ Workspace carve(void *base, int d, int D, int r, int NB)
     off += align_up((size_t)(XP_MAX_BLOCKS + 1) * NB * r * 4);     // partials, then the finished t
     w.mask = reinterpret_cast<uint64_t *>(p + off);
     off += align_up((size_t)D / 64 * 8);
-    w.idx = reinterpret_cast<int32_t *>(p + off);
-    off += align_up((size_t)D * 4);
     w.nnz = reinterpret_cast<int32_t *>(p + off);
     off += ALIGN;
     w.ypart = reinterpret_cast<float *>(p + off);
-    off += align_up((size_t)ROWS_GRID * NB * d * 4);
+    off += align_up((size_t)ROWS_BLOCKS * NB * d * 4);
     w.bytes = off;
     return w;
 }
@@ -213,9 +208,7 @@ svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_
                         float *y, hipStream_t st)
 {
     const int d = L->d, D = L->D;
-    static const int grid_env = getenv("SVDP_ROWS_GRID") ? atoi(getenv("SVDP_ROWS_GRID")) : 0;
-    int grid = ROWS_BLOCKS;
-    if (grid_env > 0 && grid_env <= ROWS_GRID) grid = grid_env;
+    const int grid = ROWS_BLOCKS;
     const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
     size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
     const size_t lds_tail = (size_t)ROWS_THREADS * 16;          // the in-launch reduction's tree
@@ -292,7 +285,7 @@ svdp_status run_step_fused(const svdp_layer *L, const void *x, int B, float *y, 
     constexpr int VEC = Elem<W>::VEC;
     uint32_t *ctrl = ctrl_for(ws_base);
     if (ctrl == nullptr) return SVDP_ERR_UNSUPPORTED;
-    const int G = g_num_cus < ROWS_GRID ? g_num_cus : ROWS_GRID;
+    const int G = g_num_cus < ROWS_BLOCKS ? g_num_cus : ROWS_BLOCKS;
     if (L->D / 64 > 4096) return SVDP_ERR_UNSUPPORTED;
     const size_t lds = fused_lds_bytes<W, NB>(L, G);
     if (lds > 160 * 1024) return SVDP_ERR_UNSUPPORTED;

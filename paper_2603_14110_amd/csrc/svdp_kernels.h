@@ -343,6 +343,11 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_compact_scan(const uint64_t *_
 //            h * W_downT[i][cols] over the chunk in list order -> ypart[g].
 //            The first rows of W_downT are requested before phase A starts.
 // Blocks with an empty chunk write nothing; block 0 records n for k_reduce_y.
+// With FINISH the kernel also performs k_reduce_y's sum inside the same launch
+// (partials written through to memory, a counter per group of blocks, a bounded
+// wait, then each block sums a 128-byte column slice); every block of the
+// launch must then be resident at once.  Measured slower than the separate
+// launch, so it is an option only.
 // max_chunk (the LDS row capacity) is a multiple of ROWS_UB.
 // Dynamic LDS: NB*d storage elements (x as stored), NB*max_chunk floats, max_chunk ints.
 // ---------------------------------------------------------------------------

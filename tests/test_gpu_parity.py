@@ -258,9 +258,9 @@ def test_active_rows_stage_alone(env):
         ws.zero_()
         binding.active_rows(c.dev, x, mask, ws=ws)
         torch.cuda.synchronize()
-        # the partial y's are the last region of the workspace: [512 blocks][NB][d] fp32, unused ones zero here
+        # the partial y's are the last region of the workspace: [256 blocks][NB][d] fp32, unused ones zero here
         NB = 1 if B == 1 else 4
-        part = ws[-512 * NB * d * 4:].view(torch.float32).view(512, NB, d)[:, :B].double().sum(dim=0)
+        part = ws[-256 * NB * d * 4:].view(torch.float32).view(256, NB, d)[:, :B].double().sum(dim=0)
         assert torch.allclose(part.float(), y, rtol=1e-4, atol=1e-5 * float(y.abs().max()))
         assert torch.equal(binding.ffn_step(c.dev, x, ws=ws), y)
 
