@@ -215,7 +215,11 @@ def measured_traffic(a):
                 out["bytes_per_step"] = float(line.split(":")[1].split()[0])
             elif line.startswith("algorithmic bytes per step"):
                 out["algorithmic_bytes_same_steps"] = float(line.split(":")[1].split()[0])
-        return out if len(out) == 2 else None
+            elif line.startswith("k_rows traffic per launch"):
+                out["rows_bytes_per_launch"] = float(line.split(":")[1].split()[0])
+            elif line.startswith("k_rows algorithmic bytes per launch"):
+                out["rows_algorithmic_bytes_same_steps"] = float(line.split(":")[1].split()[0])
+        return out if len(out) >= 2 else None
     except OSError:
         return None
 
@@ -290,7 +294,8 @@ def main():
         # the dominant kernel by itself: k_rows, algorithmic bytes = 3 matrices x active rows x d x w per launch
         ach_rows = r["bytes_rows"] / (r["us_rows"] * 1e-6) / 1e9
         roofline = {"bound": "hbm", "achieved": ach_rows, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": ach_rows / HBM_PEAK_GBS, "traffic": None,
+                    "frac": ach_rows / HBM_PEAK_GBS, "traffic": (tr or {}).get("rows_bytes_per_launch"),
+                    "traffic_algorithmic_bytes_same_launches": (tr or {}).get("rows_algorithmic_bytes_same_steps"),
                     "kernel": "k_rows (mask scan, gate/up/down over the active rows), launched alone K times from the "
                               "steps' mask words (svdp_active_rows), HIP events around the replayed graph",
                     "us_per_launch": r["us_rows"], "algorithmic_bytes_per_launch": r["bytes_rows"]}
