@@ -217,7 +217,7 @@ def measured_traffic(a):
                 out["algorithmic_bytes_same_steps"] = float(line.split(":")[1].split()[0])
             elif line.startswith("k_rows traffic per launch"):
                 out["rows_bytes_per_launch"] = float(line.split(":")[1].split()[0])
-            elif line.startswith("k_rows algorithmic bytes per launch"):
+            elif line.startswith("  launches of the kernel alone"):
                 out["rows_algorithmic_bytes_same_steps"] = float(line.split(":")[1].split()[0])
         return out if len(out) >= 2 else None
     except OSError:
