@@ -156,6 +156,23 @@ svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, 
 typedef enum { SVDP_STEP_SEQUENCE = 0, SVDP_STEP_PERSISTENT = 1, SVDP_STEP_MERGED_REDUCE = 2 } svdp_step_mode;
 void svdp_set_step_mode(int32_t mode, int32_t spin_limit);
 
+/* Which arithmetic the row kernel (gate, up, down over the list) uses (process-wide; call it
+ * while nothing is in flight).  The paper's App. C gives a row-at-a-time kernel (Alg. 3) and a
+ * gather-then-dense-contraction form (Alg. 4); its Sec. 6 notes that batching lowers the
+ * sparsity the first can exploit.
+ *  SVDP_ROWS_AUTO   (default) matrix cores for batches of 5 to 8 tokens, vector units below
+ *                   (where each was measured faster on MI355X).
+ *  SVDP_ROWS_VECTOR one wavefront per row, fp32 vector arithmetic (any dtype, batch, flags).
+ *  SVDP_ROWS_MATRIX rows taken 16 at a time as MFMA tiles straight from their place in the
+ *                   weight matrices (no gathered copy): bf16 x bf16 -> fp32 for gate and up,
+ *                   fp32 for the down projection.  Needs bf16 storage, d a multiple of 512
+ *                   and no SVDP_FLAG_REVALIDATE; other layers use SVDP_ROWS_VECTOR whatever
+ *                   is set here.
+ * Both give the same list and a y that agrees to fp32 rounding (sums are cut differently).
+ * Applies to SVDP_STEP_SEQUENCE only.                                                         */
+typedef enum { SVDP_ROWS_AUTO = 0, SVDP_ROWS_VECTOR = 1, SVDP_ROWS_MATRIX = 2 } svdp_rows_engine;
+void svdp_set_rows_engine(int32_t engine);
+
 /* Number of workspaces on which a launch gave up waiting since the last
  * call; clears the record.  Synchronises the device: not for use under capture. */
 svdp_status svdp_step_timeouts(int32_t *count);

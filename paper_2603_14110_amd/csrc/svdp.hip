@@ -6,9 +6,11 @@
 
 #include "svdp_kernels.h"
 #include "svdp_fused.h"
+#include "svdp_rows_mfma.h"
 
 #include <atomic>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 namespace {
@@ -111,6 +113,7 @@ __device__ __align__(256) uint32_t g_step_ctrl[CTRL_SLOTS * CTRL_WORDS];
 
 std::atomic<int> g_fused_mode{0};            // svdp_step_mode
 std::atomic<int> g_spin_limit{400000};       // polls before a stage wait gives up
+std::atomic<int> g_rows_engine{0};           // svdp_rows_engine
 std::mutex g_slot_mutex;
 std::vector<const void *> g_slots;
 uint32_t *g_ctrl_base = nullptr;
@@ -202,6 +205,35 @@ svdp_status launch_scores(const svdp_layer *L, const float *tpart, int nt, int B
     return launch_scores_lpr<W, NB, 6>(L, tpart, nt, B, s_out, mask_out, st);
 }
 
+// The row kernel on the matrix cores, if this layer and batch qualify: launches it and
+// returns true (status in *out); false when the vector kernel has to do the work.
+template <typename W, int NB, int MODE>
+bool launch_rows_matrix(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
+                        const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, hipStream_t st,
+                        svdp_status *out)
+{
+    if constexpr (!std::is_same<W, bf16>::value) {
+        return false;
+    } else {
+        const int engine = g_rows_engine.load();
+        // measured on the Mistral shape: ahead of the vector kernel only at the largest batch capacity
+        if (engine == SVDP_ROWS_VECTOR || (engine == SVDP_ROWS_AUTO && NB < 8)) return false;
+        if (L->d % 512 != 0 || (L->flags & SVDP_FLAG_REVALIDATE) != 0) return false;
+        const int d = L->d, D = L->D, grid = ROWS_BLOCKS;
+        const int max_chunk = ((D + grid - 1) / grid + MF_ROWS - 1) / MF_ROWS * MF_ROWS;
+        const size_t lds = (size_t)NB * d * 2 +
+                           ((size_t)ROWS_WAVES * max_chunk * 2 * NB + (size_t)max_chunk * MF_TOK + max_chunk) * 4;
+        static int granted = 64 * 1024;
+        if (lds > 160 * 1024 || allow_lds(k_rows_mfma<NB, MODE>, lds, &granted) != hipSuccess) return false;
+        hipLaunchKernelGGL((k_rows_mfma<NB, MODE>), dim3(grid), dim3(ROWS_THREADS), lds, st,
+                           static_cast<const bf16 *>(L->W_gate), static_cast<const bf16 *>(L->W_up),
+                           static_cast<const bf16 *>(L->W_downT), static_cast<const bf16 *>(x), B, d, D, mask, idx_in,
+                           nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart);
+        *out = hip_status(hipSuccess);
+        return true;
+    }
+}
+
 template <typename W, int NB, int MODE>
 svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
                         const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base,
@@ -240,11 +272,15 @@ svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_
             }
         }
     }
-    static int granted = 64 * 1024;
-    if (allow_lds(k_rows<W, NB, MODE, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_rows<W, NB, MODE, false>), dim3(grid), dim3(ROWS_THREADS), lds, st, Wg, Wu, Wd, xs, B, d, D,
-                       mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart, y, nullptr, 0);
-    svdp_status s = hip_status(hipSuccess);
+    svdp_status s;
+    if (!launch_rows_matrix<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st, &s)) {
+        static int granted = 64 * 1024;
+        if (allow_lds(k_rows<W, NB, MODE, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((k_rows<W, NB, MODE, false>), dim3(grid), dim3(ROWS_THREADS), lds, st, Wg, Wu, Wd, xs, B, d,
+                           D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart, y, nullptr,
+                           0);
+        s = hip_status(hipSuccess);
+    }
     if (s != SVDP_OK) return s;
     const int vpt = d / 4;
     const int blocks = B * ((vpt + RED_COLS - 1) / RED_COLS);
@@ -391,6 +427,8 @@ svdp_status launch_rows_only(const svdp_layer *L, const void *x, int B, const ui
     const int grid = ROWS_BLOCKS;
     const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
     const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
+    svdp_status sm;
+    if (launch_rows_matrix<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, st, &sm)) return sm;
     static int granted = 64 * 1024;
     if (allow_lds(k_rows<W, NB, ROWS_MASK, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((k_rows<W, NB, ROWS_MASK, false>), dim3(grid), dim3(ROWS_THREADS), lds, st,
@@ -531,6 +569,11 @@ void svdp_set_step_mode(int32_t mode, int32_t spin_limit)
 {
     if (mode >= SVDP_STEP_SEQUENCE && mode <= SVDP_STEP_MERGED_REDUCE) g_fused_mode.store(mode);
     if (spin_limit > 0) g_spin_limit.store(spin_limit);
+}
+
+void svdp_set_rows_engine(int32_t engine)
+{
+    if (engine >= SVDP_ROWS_AUTO && engine <= SVDP_ROWS_MATRIX) g_rows_engine.store(engine);
 }
 
 svdp_status svdp_step_timeouts(int32_t *count)

@@ -355,6 +355,76 @@ enum RowsMode { ROWS_DENSE = 0, ROWS_LIST = 1, ROWS_MASK = 2 };
 
 __device__ __forceinline__ int chunk_of(int n, int G) { return (n + G - 1) / G; }
 
+// Length n of the row list.  ROWS_MASK: every wave scans the popcounts of all mask words
+// by itself (lane l owns the wpl consecutive words starting at l*wpl), so no block-wide
+// step is needed; lane_first is the list position of the lane's first set bit.  The
+// lane's first ROWS_WREG words stay in registers (held[]) for rows_list_from_mask.
+constexpr int ROWS_WREG = 4;        // covers D <= 16384
+template <int MODE>
+__device__ __forceinline__ int rows_list_length(int D, const uint64_t *__restrict__ mask,
+                                                const int32_t *__restrict__ nnz_in, int lane, int &lane_first,
+                                                int &wpl, uint64_t (&held)[ROWS_WREG])
+{
+    lane_first = 0;
+    wpl = 0;
+    if (MODE == ROWS_DENSE) return D;
+    if (MODE == ROWS_LIST) return max(0, min(*nnz_in, D));
+    const int nwords = D / 64;
+    wpl = (nwords + 63) / 64;
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < ROWS_WREG; ++j) {
+        const int k = lane * wpl + j;
+        held[j] = (j < wpl && k < nwords) ? mask[k] : 0ull;
+        c += __popcll(held[j]);
+    }
+    for (int j = ROWS_WREG; j < wpl; ++j) {
+        const int k = lane * wpl + j;
+        if (k < nwords) c += __popcll(mask[k]);
+    }
+    const int inc = wave_inclusive_scan(c);
+    lane_first = inc - c;
+    return __builtin_amdgcn_readlane(inc, 63);
+}
+
+// Entries [lo, hi) of the ascending list of set mask bits -> lidx[0 .. hi-lo), by one wave.
+// Lane l knows where its words start in the list (lane_first).  Words that overlap
+// [lo, hi) are handed to the whole wave one at a time: lane j then looks at bit j, whose
+// list position is the word's start plus the number of set bits below it.
+__device__ __forceinline__ void rows_list_word(uint64_t w, int j, int wpl, int lane, int &p, int lo, int hi, int *lidx)
+{
+    const int pc = __popcll(w);
+    const bool overlaps = pc > 0 && p < hi && p + pc > lo;
+    uint64_t todo = __ballot(overlaps);
+    while (todo != 0ull) {
+        const int src = __ffsll((unsigned long long)todo) - 1;
+        todo &= todo - 1ull;
+        const uint32_t wlo = __builtin_amdgcn_readlane((uint32_t)w, src);
+        const uint32_t whi = __builtin_amdgcn_readlane((uint32_t)(w >> 32), src);
+        const int pk = __builtin_amdgcn_readlane(p, src);
+        const uint64_t wk = ((uint64_t)whi << 32) | wlo;
+        if ((wk >> lane) & 1ull) {
+            const int pos = pk + __popcll(wk & ((1ull << lane) - 1ull));
+            if (pos >= lo && pos < hi) lidx[pos - lo] = (src * wpl + j) * 64 + lane;
+        }
+    }
+    p += pc;
+}
+__device__ __forceinline__ void rows_list_from_mask(int D, const uint64_t *__restrict__ mask, int lane,
+                                                    int lane_first, int wpl, const uint64_t (&held)[ROWS_WREG], int lo,
+                                                    int hi, int *lidx)
+{
+    const int nwords = D / 64;
+    int p = lane_first;
+#pragma unroll
+    for (int j = 0; j < ROWS_WREG; ++j)
+        if (j < wpl) rows_list_word(held[j], j, wpl, lane, p, lo, hi, lidx);
+    for (int j = ROWS_WREG; j < wpl; ++j) {
+        const int k = lane * wpl + j;
+        rows_list_word(k < nwords ? mask[k] : 0ull, j, wpl, lane, p, lo, hi, lidx);
+    }
+}
+
 template <typename W, int NB, int MODE, bool FINISH>
 __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4))) void k_rows(
     const W *__restrict__ Wg, const W *__restrict__ Wu, const W *__restrict__ WdT, const W *__restrict__ x, int B,
@@ -385,26 +455,9 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
         xfirst[b] = (b < B && tid < nvec) ? load_raw(x + (size_t)b * d + (size_t)tid * VEC) : make_uint4(0u, 0u, 0u, 0u);
 
     // ---- the list: n, this block's chunk [lo, hi) ----
-    // ROWS_MASK: every wave scans the popcounts of all mask words by itself (lane l owns
-    // the wpl consecutive words starting at l*wpl), so no block-wide step is needed.
-    int n, lane_first = 0, wpl = 0;
-    if (MODE == ROWS_DENSE) {
-        n = D;
-    } else if (MODE == ROWS_LIST) {
-        n = max(0, min(*nnz_in, D));
-    } else {
-        const int nwords = D / 64;
-        wpl = (nwords + 63) / 64;
-        int c = 0;
-#pragma unroll 4
-        for (int j = 0; j < wpl; ++j) {
-            const int k = lane * wpl + j;
-            if (k < nwords) c += __popcll(mask[k]);
-        }
-        const int inc = wave_inclusive_scan(c);
-        lane_first = inc - c;
-        n = __builtin_amdgcn_readlane(inc, 63);
-    }
+    int lane_first, wpl;
+    uint64_t held[ROWS_WREG];
+    const int n = rows_list_length<MODE>(D, mask, nnz_in, lane, lane_first, wpl, held);
     SVDP_STAMP(2, 1);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -431,32 +484,7 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
         for (int q = tid; q < padded; q += ROWS_THREADS) lidx[q] = idx_in[lo + min(q, cnt - 1)];
     } else if (MODE == ROWS_MASK) {
         if (wave == 0) {
-            // Lane l knows where its words start in the list (lane_first).  Words that
-            // overlap [lo, hi) are handed to the whole wave one at a time: lane j then
-            // looks at bit j, whose list position is the word's start plus the number
-            // of set bits below it.
-            const int nwords = D / 64;
-            int p = lane_first;
-            for (int j = 0; j < wpl; ++j) {
-                const int k = lane * wpl + j;
-                const uint64_t w = k < nwords ? mask[k] : 0ull;
-                const int pc = __popcll(w);
-                const bool overlaps = pc > 0 && p < hi && p + pc > lo;
-                uint64_t todo = __ballot(overlaps);
-                while (todo != 0ull) {
-                    const int src = __ffsll((unsigned long long)todo) - 1;
-                    todo &= todo - 1ull;
-                    const uint32_t wlo = __builtin_amdgcn_readlane((uint32_t)w, src);
-                    const uint32_t whi = __builtin_amdgcn_readlane((uint32_t)(w >> 32), src);
-                    const int pk = __builtin_amdgcn_readlane(p, src);
-                    const uint64_t wk = ((uint64_t)whi << 32) | wlo;
-                    if ((wk >> lane) & 1ull) {
-                        const int pos = pk + __popcll(wk & ((1ull << lane) - 1ull));
-                        if (pos >= lo && pos < hi) lidx[pos - lo] = (src * wpl + j) * 64 + lane;
-                    }
-                }
-                p += pc;
-            }
+            rows_list_from_mask(D, mask, lane, lane_first, wpl, held, lo, hi, lidx);
             // same wave, LDS is in order: the last real entry is visible to the padding
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();

@@ -1,0 +1,258 @@
+// Gate, up and down over a list of rows on the matrix cores, for batches of
+// several tokens in bf16 storage (the regime the paper's Sec. 6 names as the
+// limit of the sparse path: the union of the tokens' masks is dense enough that
+// a row-at-a-time kernel spends its time in per-token vector arithmetic, and
+// App. C's Alg. 4 treats the selected rows as a small dense contraction).
+// Same contract, list handling and partial-y layout as k_rows; only the
+// arithmetic differs:
+//   phase A: tiles of 16 list rows x 64 elements of d; four lanes fetch 64
+//            contiguous bytes of one row per load, two loads cover 128 bytes and
+//            feed two v_mfma_f32_16x16x32_bf16 per matrix, whose other operand
+//            is x in LDS, stored in operand order.  The eight waves of the block
+//            split d between them; their 16x16 partial tiles meet in LDS and are
+//            added in wave order, then h = ReLU(g)*u.
+//   phase B: y[token][col] += h[token][row] * W_downT[row][col] as fp32 outer
+//            products, v_mfma_f32_4x4x1_16b_f32: a wave's 16-byte-per-lane load
+//            is 1 KB of one row (512 columns); after widening to fp32 each of
+//            the eight columns of a lane goes through one instruction per group
+//            of four tokens, and h stays fp32.  A wave owns 512-column tiles and
+//            walks the chunk row by row, MF_UB rows in flight, the first of them
+//            requested before phase A's results are combined.
+// Products of bf16 values are exact in fp32 and every sum has a fixed order.
+// Requirements checked by the host: d % 512 == 0, NB <= 8.
+// Dynamic LDS: NB*d*2 bytes (x) + ROWS_WAVES*max_chunk*2*NB floats (partial
+// tiles) + max_chunk*16 floats (h) + max_chunk ints (list); max_chunk % 16 == 0.
+#pragma once
+
+#include "svdp_kernels.h"
+
+namespace svdp {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+constexpr int MF_ROWS = 16;      // list rows per phase-A tile
+constexpr int MF_TOK = 16;       // token slots of a tile (slots >= NB are padding)
+constexpr int MF_UA = 4;         // phase A: 64-element steps fetched together
+constexpr int MF_UB = 8;         // phase B: rows fetched together
+constexpr int MF_COLS = 512;     // phase B: columns per wave tile (eight per lane)
+
+__device__ __forceinline__ f32x4_t mfma_bf16(const uint4 &a, const uint4 &b, f32x4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                   0, 0, 0);
+}
+
+template <int NB, int MODE>
+__global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
+    const bf16 *__restrict__ Wg, const bf16 *__restrict__ Wu, const bf16 *__restrict__ WdT,
+    const bf16 *__restrict__ x, int B, int d, int D, const uint64_t *__restrict__ mask,
+    const int32_t *__restrict__ idx_in, const int32_t *__restrict__ nnz_in, int32_t *__restrict__ idx_out,
+    int32_t *__restrict__ nnz_out, int32_t *__restrict__ n_used, int max_chunk, uint32_t flags,
+    float *__restrict__ ypart)
+{
+    static_assert(NB == 1 || NB == 2 || NB == 4 || NB == 8, "token slots are addressed with a mask");
+    extern __shared__ uint4 smem16[];
+    const int nvec = d / 8;                                        // 16-byte vectors per token
+    const int nsteps = d / 64;                                     // phase-A steps per row
+    uint4 *xs = smem16;                                            // [nsteps][2][4][NB], operand order
+    float *part = reinterpret_cast<float *>(xs + NB * nvec);       // [ROWS_WAVES][tiles][2][16][NB]
+    float *hs = part + (size_t)ROWS_WAVES * max_chunk * 2 * NB;    // [max_chunk][MF_TOK]
+    int *lidx = reinterpret_cast<int *>(hs + (size_t)max_chunk * MF_TOK);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lm = lane & 15, lq = lane >> 4;
+    const int G = gridDim.x;
+    SVDP_STAMP(2, 0);
+
+    // ---- request x; the vector of element 8c..8c+7 goes where the lane that needs it as an
+    // operand will read it: step c/8, instruction (c/4)%2, lane quarter c%4, token ----
+    auto xslot = [&](int c, int b) -> int { return (((c >> 3) * 2 + ((c >> 2) & 1)) * 4 + (c & 3)) * NB + b; };
+    uint4 xfirst[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+        xfirst[b] = (b < B && tid < nvec) ? load_raw(x + (size_t)b * d + (size_t)tid * 8) : make_uint4(0u, 0u, 0u, 0u);
+
+    int lane_first, wpl;
+    uint64_t held[ROWS_WREG];
+    const int n = rows_list_length<MODE>(D, mask, nnz_in, lane, lane_first, wpl, held);
+    SVDP_STAMP(2, 1);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (tid < nvec) xs[xslot(tid, b)] = xfirst[b];
+        for (int c = tid + ROWS_THREADS; c < nvec; c += ROWS_THREADS)
+            xs[xslot(c, b)] = b < B ? load_raw(x + (size_t)b * d + (size_t)c * 8) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    const int chunk = chunk_of(n, G);
+    const int lo = min(n, (int)blockIdx.x * chunk);
+    const int hi = min(n, lo + chunk);
+    const int cnt = hi - lo;
+    if (blockIdx.x == 0 && tid == 0) {
+        if (MODE != ROWS_DENSE) *n_used = n;
+        if (MODE == ROWS_MASK && nnz_out != nullptr) *nnz_out = n;
+    }
+    if (cnt <= 0) return;
+
+    if (MODE == ROWS_LIST) {
+        for (int q = tid; q < cnt; q += ROWS_THREADS) lidx[q] = idx_in[lo + q];
+    } else if (MODE == ROWS_MASK) {
+        if (wave == 0) rows_list_from_mask(D, mask, lane, lane_first, wpl, held, lo, hi, lidx);
+    }
+    __syncthreads();
+    SVDP_STAMP(2, 2);
+    if (MODE == ROWS_MASK && idx_out != nullptr)
+        for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
+
+    const bool drelu = (flags & 1u) != 0;
+    // rows past the end of the chunk repeat its last row; their h is zero
+    auto row_of = [&](int q) -> size_t {
+        const int qq = min(q, cnt - 1);
+        return MODE == ROWS_DENSE ? (size_t)(lo + qq) : (size_t)lidx[qq];
+    };
+    const int ntile = (cnt + MF_ROWS - 1) / MF_ROWS;
+
+    // ---- phase A: this wave's share of d is the steps [wave*spw, (wave+1)*spw) ----
+    const int spw = nsteps / ROWS_WAVES;
+    const int tb = lm & (NB - 1);                                   // token slot read as the x operand
+    for (int t = 0; t < ntile; ++t) {
+        const size_t row = row_of(t * MF_ROWS + lm);
+        const bf16 *pg = Wg + row * d + (size_t)wave * spw * 64 + lq * 8;
+        const bf16 *pu = Wu + row * d + (size_t)wave * spw * 64 + lq * 8;
+        f32x4_t ag = {0.f, 0.f, 0.f, 0.f}, au = {0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < spw; s0 += MF_UA) {
+            uint4 g0[MF_UA], g1[MF_UA], u0[MF_UA], u1[MF_UA];
+#pragma unroll
+            for (int k = 0; k < MF_UA; ++k) {
+                if (s0 + k < spw) {
+                    g0[k] = load_raw(pg + (size_t)(s0 + k) * 64);
+                    g1[k] = load_raw(pg + (size_t)(s0 + k) * 64 + 32);
+                    u0[k] = load_raw(pu + (size_t)(s0 + k) * 64);
+                    u1[k] = load_raw(pu + (size_t)(s0 + k) * 64 + 32);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < MF_UA; ++k) {
+                if (s0 + k < spw) {
+                    const int s = wave * spw + s0 + k;
+                    const uint4 xa = xs[((s * 2 + 0) * 4 + lq) * NB + tb];
+                    const uint4 xb = xs[((s * 2 + 1) * 4 + lq) * NB + tb];
+                    ag = mfma_bf16(g0[k], xa, ag);
+                    au = mfma_bf16(u0[k], xa, au);
+                    ag = mfma_bf16(g1[k], xb, ag);
+                    au = mfma_bf16(u1[k], xb, au);
+                }
+            }
+        }
+        // the lane holds rows 4*lq .. 4*lq+3 of the tile for token lm
+        if (lm < NB) {
+            float *pt = part + ((size_t)(wave * ntile + t) * 2) * MF_ROWS * NB;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                pt[(lq * 4 + i) * NB + lm] = ag[i];
+                pt[MF_ROWS * NB + (lq * 4 + i) * NB + lm] = au[i];
+            }
+        }
+    }
+    // ---- phase B's first loads, requested before the waves meet.  A unit is one row of the
+    // chunk over one 512-column tile (tiles wave, wave + ROWS_WAVES, ...) ----
+    const int nct = d / MF_COLS;
+    const int nu = ((nct - wave + ROWS_WAVES - 1) / ROWS_WAVES) * cnt;    // units of this wave
+    auto unit_ptr = [&](int j, int q) -> const bf16 * {
+        return WdT + row_of(q) * d + (size_t)(wave + j * ROWS_WAVES) * MF_COLS + (size_t)lane * 8;
+    };
+    int ji = 0, qi = 0;                                             // next unit to request
+    uint4 cur[MF_UB];
+#pragma unroll
+    for (int k = 0; k < MF_UB; ++k) {
+        if (k < nu) {
+            cur[k] = load_raw(unit_ptr(ji, qi));
+            if (++qi == cnt) { qi = 0; ++ji; }
+        }
+    }
+    SVDP_STAMP(2, 3);
+    __syncthreads();
+    // partial tiles of the waves, added in wave order -> h[row][token slot]
+    for (int e = tid; e < ntile * MF_ROWS * MF_TOK; e += ROWS_THREADS) {
+        const int q = e / MF_TOK, b = e % MF_TOK;
+        float h = 0.f;
+        if (b < NB && q < cnt) {
+            const int t = q / MF_ROWS, rr = q % MF_ROWS;
+            float gs = 0.f, us = 0.f;
+#pragma unroll
+            for (int w = 0; w < ROWS_WAVES; ++w) {
+                const float *pt = part + ((size_t)(w * ntile + t) * 2) * MF_ROWS * NB;
+                gs += pt[rr * NB + b];
+                us += pt[MF_ROWS * NB + rr * NB + b];
+            }
+            h = fmaxf(gs, 0.f) * (drelu ? fmaxf(us, 0.f) : us);
+        }
+        hs[e] = h;
+    }
+    __syncthreads();
+    SVDP_STAMP(2, 4);
+
+    // ---- phase B: the wave's units are walked in one sequence, MF_UB of them fetched ahead, so
+    // that the loads of the next column tile are in flight while the current one is finished.
+    // v_mfma_f32_4x4x1_16b: sixteen independent 4x4 outer products; block l/4 of lane l gets
+    // (h of four tokens for this row) x (the lane's and its three neighbours' weights), and the
+    // lane keeps the four tokens' sums for its own column ----
+    {
+        constexpr int TG = (NB + 3) / 4;                            // groups of four tokens
+        f32x4_t acc[TG][8];
+#pragma unroll
+        for (int g = 0; g < TG; ++g)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[g][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        int jc = 0, qc = 0;                                         // unit being computed
+        for (int base = 0; base < nu; base += MF_UB) {
+            uint4 nxt[MF_UB];
+#pragma unroll
+            for (int k = 0; k < MF_UB; ++k) {
+                if (base + MF_UB + k < nu) {
+                    nxt[k] = load_raw(unit_ptr(ji, qi));
+                    if (++qi == cnt) { qi = 0; ++ji; }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < MF_UB; ++k) {
+                if (base + k < nu) {
+                    float a[TG];
+#pragma unroll
+                    for (int g = 0; g < TG; ++g) a[g] = hs[qc * MF_TOK + g * 4 + (lane & 3)];
+                    float w[8];
+                    widen(cur[k], w, (const bf16 *)nullptr);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+#pragma unroll
+                        for (int g = 0; g < TG; ++g)
+                            acc[g][e] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[g], w[e], acc[g][e], 0, 0, 0);
+                    if (++qc == cnt) {
+                        // register i of a group holds token 4g+i for columns ct*512 + lane*8 + e
+                        const int ct = wave + jc * ROWS_WAVES;
+#pragma unroll
+                        for (int g = 0; g < TG; ++g)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int b = g * 4 + i;
+                                if (b < NB) {
+                                    float4 *out = reinterpret_cast<float4 *>(ypart + ((size_t)blockIdx.x * NB + b) * d +
+                                                                             (size_t)ct * MF_COLS + (size_t)lane * 8);
+                                    out[0] = make_float4(acc[g][0][i], acc[g][1][i], acc[g][2][i], acc[g][3][i]);
+                                    out[1] = make_float4(acc[g][4][i], acc[g][5][i], acc[g][6][i], acc[g][7][i]);
+                                }
+                            }
+#pragma unroll
+                        for (int g = 0; g < TG; ++g)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) acc[g][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                        qc = 0;
+                        ++jc;
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < MF_UB; ++k) cur[k] = nxt[k];
+        }
+    }
+    SVDP_STAMP(2, 5);
+}
+
+}   // namespace svdp

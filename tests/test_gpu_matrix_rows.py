@@ -1,0 +1,148 @@
+"""GPU parity of the row kernel on the matrix cores (svdp_set_rows_engine) against
+the CPU oracle: every entry point that runs it, on seeded random layers whose row
+chunks span several 16-row tiles with ragged ends, for every batch size."""
+import numpy as np
+import pytest
+
+import parity
+from paper_2603_14110_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(oracle):
+    import torch
+    from paper_2603_14110_amd import binding
+
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    binding.lib()
+    yield binding, torch, oracle
+    binding.set_rows_engine(binding.ROWS_AUTO)
+
+
+class RandomLayer:
+    """Plain random bf16 layer (no generator structure): weights ~ N(0, 1/d), a bias that keeps
+    about a third of the neurons on."""
+
+    def __init__(self, binding, torch, seed, d, D, r, B):
+        rng = np.random.default_rng(seed)
+        dt = "bf16"
+        st = lambda a: synth.to_storage(a, dt)
+        Wg, Wu, Wd = (st(rng.standard_normal((D, d)) / np.sqrt(d)) for _ in range(3))
+        P, Q = st(rng.standard_normal((d, r)) / np.sqrt(d)), st(rng.standard_normal((D, r)))
+        self.b = (rng.standard_normal(D) * 0.5 - 1.5).astype(np.float32)
+        X = st(rng.standard_normal((B, d)))
+        self.f = {k: synth.storage_to_f32(v, dt) for k, v in dict(W_gate=Wg, W_up=Wu, W_downT=Wd, P=P, Q=Q).items()}
+        self.X = synth.storage_to_f32(X, dt)
+        self.dev = binding.DeviceLayer(*(binding.to_device(a, dt) for a in (P, Q)), torch.from_numpy(self.b).cuda(),
+                                       *(binding.to_device(a, dt) for a in (Wg, Wu, Wd)))
+        self.Xd = binding.to_device(X, dt)
+        self.d, self.D, self.B = d, D, B
+
+
+# (d, D, r, B): d a multiple of 512; D/256 from under one tile to several tiles with a ragged end
+SHAPES = [(512, 64, 8, 1), (512, 4160, 16, 8), (1024, 8704, 72, 8), (1536, 12352, 40, 5), (1024, 5184, 24, 4),
+          (2048, 4608, 32, 3), (512, 16448, 16, 7), (1024, 2560, 64, 2), (3584, 6400, 48, 6), (512, 10048, 96, 8)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_matrix_engine_every_entry_point(env, shape):
+    binding, torch, oracle = env
+    d, D, r, B = shape
+    c = RandomLayer(binding, torch, 77 + D, d, D, r, B)
+    f = c.f
+    s_or = oracle.predict(f["P"], f["Q"], c.b, c.X)
+    results = {}
+    for engine in (binding.ROWS_MATRIX, binding.ROWS_VECTOR):
+        binding.set_rows_engine(engine)
+        # the whole step
+        mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+        idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+        nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+        y = binding.ffn_step(c.dev, c.Xd, mask=mask, idx=idx, nnz=nnz)
+        lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+        y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X, lst)
+        parity.check_y(y.cpu().numpy(), y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X, lst))
+        assert torch.equal(y, binding.ffn_step(c.dev, c.Xd))            # optional outputs change nothing
+        # dense baseline
+        yd = binding.dense_ffn(c.dev, c.Xd)
+        parity.check_y(yd.cpu().numpy(), oracle.dense_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X), "bf16",
+                       slack=parity.fp32_forward_bound(f, c.X, np.arange(D)))
+        # dReLU variant
+        dl = c.dev.with_flags(binding.FLAG_DRELU)
+        mask2 = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+        idx2 = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+        nnz2 = torch.zeros(1, dtype=torch.int32, device="cuda")
+        y2 = binding.ffn_step(dl, c.Xd, mask=mask2, idx=idx2, nnz=nnz2)
+        lst2 = parity.check_mask_and_idx(s_or, mask2.cpu().numpy(), idx2.cpu().numpy(), nnz2.item(), D)
+        parity.check_y(y2.cpu().numpy(),
+                       oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X, lst2, drelu=True), "bf16",
+                       slack=parity.fp32_forward_bound(f, c.X, lst2))
+        results[engine] = (lst, y.cpu().numpy(), yd.cpu().numpy())
+    # the two engines: same list, y equal to fp32 rounding
+    assert np.array_equal(results[binding.ROWS_MATRIX][0], results[binding.ROWS_VECTOR][0])
+    for k in (1, 2):
+        a, b = results[binding.ROWS_MATRIX][k].astype(np.float64), results[binding.ROWS_VECTOR][k].astype(np.float64)
+        assert np.linalg.norm(a - b) <= 2e-5 * max(np.linalg.norm(b), 1e-30)
+    binding.set_rows_engine(binding.ROWS_AUTO)
+
+
+@pytest.mark.parametrize("shape", SHAPES[1:4])
+def test_matrix_engine_arbitrary_lists(env, shape):
+    binding, torch, oracle = env
+    d, D, r, B = shape
+    c = RandomLayer(binding, torch, 5 + D, d, D, r, 8)
+    f = c.f
+    rng = np.random.default_rng(D)
+    lists = [np.zeros(0, np.int32), np.array([D - 1], np.int32), np.arange(D, dtype=np.int32),
+             np.arange(0, D, 17, dtype=np.int32), np.sort(rng.choice(D, D // 2 + 3, replace=False)).astype(np.int32),
+             np.sort(rng.choice(D, 255, replace=False)).astype(np.int32),          # fewer rows than blocks
+             np.sort(rng.choice(D, 257, replace=False)).astype(np.int32),
+             rng.permutation(D)[: D // 7].astype(np.int32)]                        # unsorted lists are allowed
+    binding.set_rows_engine(binding.ROWS_MATRIX)
+    try:
+        for Bq in (1, 2, 3, 4, 8):
+            for lst in lists:
+                idx = torch.zeros(D, dtype=torch.int32, device="cuda")
+                idx[: lst.size] = torch.from_numpy(lst).cuda()
+                nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
+                y = binding.sparse_ffn(c.dev, c.Xd[:Bq], idx, nnz).cpu().numpy()
+                y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X[:Bq], lst)
+                parity.check_y(y, y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X[:Bq], lst))
+                if lst.size == 0:
+                    assert not y.any()
+    finally:
+        binding.set_rows_engine(binding.ROWS_AUTO)
+
+
+def test_engine_selection_and_determinism(env):
+    """AUTO = matrix cores from 5 tokens up (batch capacity 8), vector units below; layers the matrix kernel does not
+    take (fp32 storage, d not a multiple of 512, re-validation) run on the vector kernel whatever
+    is set.  Seen through bit patterns: each engine is deterministic and the two differ in the
+    last bits of y."""
+    binding, torch, oracle = env
+    c = RandomLayer(binding, torch, 11, 1024, 8704, 32, 8)
+
+    def run(engine, B, dev=None):
+        binding.set_rows_engine(engine)
+        y = binding.ffn_step(dev or c.dev, c.Xd[:B]).clone()
+        binding.set_rows_engine(binding.ROWS_AUTO)
+        return y
+
+    for B in (1, 2, 3, 4, 5, 8):
+        ym, yv, ya = run(binding.ROWS_MATRIX, B), run(binding.ROWS_VECTOR, B), run(binding.ROWS_AUTO, B)
+        assert torch.equal(ym, run(binding.ROWS_MATRIX, B)) and torch.equal(yv, run(binding.ROWS_VECTOR, B))
+        assert not torch.equal(ym, yv)
+        assert torch.equal(ya, ym if B >= 5 else yv)
+    # re-validation: vector kernel under every setting
+    dv = c.dev.with_flags(binding.FLAG_REVALIDATE)
+    assert torch.equal(run(binding.ROWS_MATRIX, 8, dv), run(binding.ROWS_VECTOR, 8, dv))
+    # d = 520: not a multiple of 512
+    c2 = RandomLayer(binding, torch, 12, 520, 4160, 16, 8)
+    binding.set_rows_engine(binding.ROWS_MATRIX)
+    y1 = binding.ffn_step(c2.dev, c2.Xd).clone()
+    binding.set_rows_engine(binding.ROWS_VECTOR)
+    y2 = binding.ffn_step(c2.dev, c2.Xd).clone()
+    binding.set_rows_engine(binding.ROWS_AUTO)
+    assert torch.equal(y1, y2)
