@@ -42,8 +42,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=16, help="weight copies rotated through (1 = hot cache)")
     ap.add_argument("--reps", type=int, default=5, help="graph replays; the median is reported")
     ap.add_argument("--flags", type=int, default=0)
-    ap.add_argument("--rows-engine", default="auto", choices=["auto", "vector", "matrix"],
-                    help="arithmetic of the row kernel (svdp_set_rows_engine)")
+    ap.add_argument("--engine", default="auto", choices=["auto", "vector", "matrix"],
+                    help="arithmetic units of the batch-sensitive kernels (svdp_set_engine)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
@@ -276,8 +276,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     binding.lib()
-    binding.set_rows_engine({"auto": binding.ROWS_AUTO, "vector": binding.ROWS_VECTOR,
-                             "matrix": binding.ROWS_MATRIX}[a.rows_engine])
+    binding.set_engine({"auto": binding.ENGINE_AUTO, "vector": binding.ENGINE_VECTOR,
+                             "matrix": binding.ENGINE_MATRIX}[a.engine])
     if a.table4:
         table4(a)
         return
@@ -323,7 +323,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": r["workload"], "batch": B, "layers": Lyr, "weight_copies": r["copies"],
                    "cache_mode": r["cache_mode"], "flags": a.flags, "graph": not a.no_graph,
-                   "rows_engine": a.rows_engine,
+                   "engine": a.engine,
                    "storage": "bf16 weights/tokens, f32 accumulate" if r["dtype"] == "bf16" else "f32"},
         "density_mean": float(dens.mean()),
         "density_percentiles_0_5_50_95_100": [float(np.percentile(dens, p)) for p in (0, 5, 50, 95, 100)],

@@ -156,22 +156,27 @@ svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, 
 typedef enum { SVDP_STEP_SEQUENCE = 0, SVDP_STEP_PERSISTENT = 1, SVDP_STEP_MERGED_REDUCE = 2 } svdp_step_mode;
 void svdp_set_step_mode(int32_t mode, int32_t spin_limit);
 
-/* Which arithmetic the row kernel (gate, up, down over the list) uses (process-wide; call it
- * while nothing is in flight).  The paper's App. C gives a row-at-a-time kernel (Alg. 3) and a
+/* Which arithmetic units the batch-sensitive kernels use (process-wide; call it while nothing
+ * is in flight).  The paper's App. C gives a row-at-a-time kernel (Alg. 3) and a
  * gather-then-dense-contraction form (Alg. 4); its Sec. 6 notes that batching lowers the
  * sparsity the first can exploit.
- *  SVDP_ROWS_AUTO   (default) matrix cores for batches of 5 to 8 tokens, vector units below
- *                   (where each was measured faster on MI355X).
- *  SVDP_ROWS_VECTOR one wavefront per row, fp32 vector arithmetic (any dtype, batch, flags).
- *  SVDP_ROWS_MATRIX rows taken 16 at a time as MFMA tiles straight from their place in the
- *                   weight matrices (no gathered copy): bf16 x bf16 -> fp32 for gate and up,
- *                   fp32 for the down projection.  Needs bf16 storage, d a multiple of 512
- *                   and no SVDP_FLAG_REVALIDATE; other layers use SVDP_ROWS_VECTOR whatever
- *                   is set here.
- * Both give the same list and a y that agrees to fp32 rounding (sums are cut differently).
- * Applies to SVDP_STEP_SEQUENCE only.                                                         */
-typedef enum { SVDP_ROWS_AUTO = 0, SVDP_ROWS_VECTOR = 1, SVDP_ROWS_MATRIX = 2 } svdp_rows_engine;
-void svdp_set_rows_engine(int32_t engine);
+ *  SVDP_ENGINE_AUTO   (default) per kernel and batch capacity, whichever was measured faster on
+ *                     MI355X: matrix cores for the scores from 3 tokens and for the rows from
+ *                     5 tokens, vector units below.
+ *  SVDP_ENGINE_VECTOR fp32 vector arithmetic everywhere (any dtype, batch, flags).
+ *  SVDP_ENGINE_MATRIX matrix cores wherever a kernel for them exists:
+ *                     - rows (gate, up, down over the list): taken 16 at a time as MFMA tiles
+ *                       straight from their place in the weight matrices (no gathered copy),
+ *                       bf16 x bf16 -> fp32 for gate and up, fp32 outer products for the down
+ *                       projection; needs bf16 storage, d a multiple of 512 and no
+ *                       SVDP_FLAG_REVALIDATE;
+ *                     - scores (t Q^T + b): bf16 MFMAs with t split into three bf16 terms
+ *                       (exact to fp32); needs bf16 storage, r a multiple of 32, r <= 512.
+ *                     Layers that do not qualify use the vector kernels whatever is set here.
+ * Both give the same mask and list (up to scores within rounding of zero) and a y that agrees
+ * to fp32 rounding (sums are cut differently).  Applies to SVDP_STEP_SEQUENCE only.          */
+typedef enum { SVDP_ENGINE_AUTO = 0, SVDP_ENGINE_VECTOR = 1, SVDP_ENGINE_MATRIX = 2 } svdp_engine;
+void svdp_set_engine(int32_t engine);
 
 /* Number of workspaces on which a launch gave up waiting since the last
  * call; clears the record.  Synchronises the device: not for use under capture. */

@@ -23,7 +23,7 @@ MAX_BATCH = 8
 EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
     "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version", "svdp_set_step_mode",
-    "svdp_step_timeouts", "svdp_active_rows", "svdp_set_rows_engine",
+    "svdp_step_timeouts", "svdp_active_rows", "svdp_set_engine",
 ]
 
 
@@ -72,8 +72,8 @@ def lib() -> ctypes.CDLL:
     L.svdp_version.restype = ctypes.c_char_p
     L.svdp_set_step_mode.argtypes = [i32, i32]
     L.svdp_set_step_mode.restype = None
-    L.svdp_set_rows_engine.argtypes = [i32]
-    L.svdp_set_rows_engine.restype = None
+    L.svdp_set_engine.argtypes = [i32]
+    L.svdp_set_engine.restype = None
     L.svdp_step_timeouts.argtypes = [ctypes.POINTER(ctypes.c_int32)]
     L.svdp_step_timeouts.restype = ctypes.c_int
     _lib = L
@@ -244,11 +244,11 @@ def set_step_mode(mode: int, spin_limit: int = 0) -> None:
     lib().svdp_set_step_mode(int(mode), int(spin_limit))
 
 
-ROWS_AUTO, ROWS_VECTOR, ROWS_MATRIX = 0, 1, 2
+ENGINE_AUTO, ENGINE_VECTOR, ENGINE_MATRIX = 0, 1, 2
 
 
-def set_rows_engine(engine: int) -> None:
-    lib().svdp_set_rows_engine(int(engine))
+def set_engine(engine: int) -> None:
+    lib().svdp_set_engine(int(engine))
 
 
 def step_timeouts() -> int:

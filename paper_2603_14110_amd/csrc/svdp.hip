@@ -113,7 +113,7 @@ __device__ __align__(256) uint32_t g_step_ctrl[CTRL_SLOTS * CTRL_WORDS];
 
 std::atomic<int> g_fused_mode{0};            // svdp_step_mode
 std::atomic<int> g_spin_limit{400000};       // polls before a stage wait gives up
-std::atomic<int> g_rows_engine{0};           // svdp_rows_engine
+std::atomic<int> g_engine{0};           // svdp_engine
 std::mutex g_slot_mutex;
 std::vector<const void *> g_slots;
 uint32_t *g_ctrl_base = nullptr;
@@ -194,10 +194,28 @@ svdp_status launch_scores_lpr(const svdp_layer *L, const float *tpart, int nt, i
     return launch_scores_thr<W, NB, LPR_LOG2, 256>(L, tpart, nt, B, s_out, mask_out, st);
 }
 
+// Whether the score kernel on the matrix cores takes this layer and batch capacity.
+template <typename W, int NB>
+bool scores_on_matrix(const svdp_layer *L)
+{
+    if (!std::is_same<W, bf16>::value) return false;
+    const int engine = g_engine.load();
+    const bool want = engine == SVDP_ENGINE_MATRIX || (engine == SVDP_ENGINE_AUTO && NB >= 4);
+    return want && L->r % 32 == 0 && L->r <= 32 * SCM_KB;
+}
+
 template <typename W, int NB>
 svdp_status launch_scores(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
                           uint64_t *mask_out, hipStream_t st)
 {
+    if constexpr (std::is_same<W, bf16>::value) {
+        if (scores_on_matrix<W, NB>(L)) {
+            const size_t lds = (size_t)3 * NB * L->r * 2;
+            hipLaunchKernelGGL((k_scores_mfma<NB>), dim3(L->D / SC_SLAB), dim3(SCM_THREADS), lds, st,
+                               static_cast<const bf16 *>(L->Q), L->b, tpart, nt, B, L->D, L->r, s_out, mask_out);
+            return hip_status(hipSuccess);
+        }
+    }
     const int cg = L->r / Elem<W>::VEC;       // 16-byte column groups per row of Q
     if (cg <= 8) return launch_scores_lpr<W, NB, 3>(L, tpart, nt, B, s_out, mask_out, st);
     if (cg <= 16) return launch_scores_lpr<W, NB, 4>(L, tpart, nt, B, s_out, mask_out, st);
@@ -215,9 +233,9 @@ bool launch_rows_matrix(const svdp_layer *L, const void *x, int B, const uint64_
     if constexpr (!std::is_same<W, bf16>::value) {
         return false;
     } else {
-        const int engine = g_rows_engine.load();
+        const int engine = g_engine.load();
         // measured on the Mistral shape: ahead of the vector kernel only at the largest batch capacity
-        if (engine == SVDP_ROWS_VECTOR || (engine == SVDP_ROWS_AUTO && NB < 8)) return false;
+        if (engine == SVDP_ENGINE_VECTOR || (engine == SVDP_ENGINE_AUTO && NB < 8)) return false;
         if (L->d % 512 != 0 || (L->flags & SVDP_FLAG_REVALIDATE) != 0) return false;
         const int d = L->d, D = L->D, grid = ROWS_BLOCKS;
         const int max_chunk = ((D + grid - 1) / grid + MF_ROWS - 1) / MF_ROWS * MF_ROWS;
@@ -377,8 +395,9 @@ svdp_status run_predict(const svdp_layer *L, const void *x, int B, float *s, uin
     int nt = 0;
     svdp_status e = launch_xP<W, NB>(L, x, B, w.tpart, &nt, st);
     if (e != SVDP_OK) return e;
-    if (NB >= 4 && nt > 1) {
-        // finish t once instead of in every score block
+    if (NB >= 4 && nt > 1 && !scores_on_matrix<W, NB>(L)) {
+        // finish t once instead of in every score block (the vector score kernel splits the
+        // partial list over threads through LDS, which costs more than a launch from 4 tokens up)
         const int count = NB * L->r;
         float *t = w.tpart + (size_t)XP_MAX_BLOCKS * NB * L->r;
         hipLaunchKernelGGL(k_tsum, dim3((count + 255) / 256), dim3(256), 0, st, w.tpart, nt, count, t);
@@ -571,9 +590,9 @@ void svdp_set_step_mode(int32_t mode, int32_t spin_limit)
     if (spin_limit > 0) g_spin_limit.store(spin_limit);
 }
 
-void svdp_set_rows_engine(int32_t engine)
+void svdp_set_engine(int32_t engine)
 {
-    if (engine >= SVDP_ROWS_AUTO && engine <= SVDP_ROWS_MATRIX) g_rows_engine.store(engine);
+    if (engine >= SVDP_ENGINE_AUTO && engine <= SVDP_ENGINE_MATRIX) g_engine.store(engine);
 }
 
 svdp_status svdp_step_timeouts(int32_t *count)

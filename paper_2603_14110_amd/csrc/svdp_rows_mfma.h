@@ -1,4 +1,6 @@
-// Gate, up and down over a list of rows on the matrix cores, for batches of
+// Kernels on the matrix cores.
+//
+// k_rows_mfma: gate, up and down over a list of rows, for batches of
 // several tokens in bf16 storage (the regime the paper's Sec. 6 names as the
 // limit of the sparse path: the union of the tokens' masks is dense enough that
 // a row-at-a-time kernel spends its time in per-token vector arithmetic, and
@@ -253,6 +255,118 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
         }
     }
     SVDP_STAMP(2, 5);
+}
+
+// ---------------------------------------------------------------------------
+// Predictor stage 2 on the matrix cores: s_i = t . Q[i,:] + b_i for a slab of
+// 64 neurons and up to eight tokens, and the slab's mask word (eq. 2).  One
+// wave per 16 rows of Q; a lane fetches 16 bytes of one row per 32 columns
+// (all requested before t is touched).  t (fp32, the sum of the nt stage-1
+// partials) is split into three bf16 terms hi + mid + lo = t exactly to 24 bits,
+// stored in LDS in operand order, so that bf16 MFMAs give fp32-accurate scores:
+// every product is exact and the accumulation is fp32.
+// Requirements checked by the host: r % 32 == 0, r <= 32 * SCM_KB.
+// Dynamic LDS: 3 * NB * r * 2 bytes.
+// ---------------------------------------------------------------------------
+constexpr int SCM_THREADS = 256;
+constexpr int SCM_KB = 16;          // 32-column blocks of Q held in registers
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float v)
+{
+    bf16 h;
+    from_f32(v, &h);
+    return h.bits;
+}
+
+template <int NB>
+__global__ __launch_bounds__(SCM_THREADS) void k_scores_mfma(const bf16 *__restrict__ Q, const float *__restrict__ bias,
+                                                             const float *__restrict__ tpart, int nt, int B, int D,
+                                                             int r, float *__restrict__ s_out,
+                                                             uint64_t *__restrict__ mask_out)
+{
+    static_assert(NB == 1 || NB == 2 || NB == 4 || NB == 8, "token slots are addressed with a mask");
+    extern __shared__ uint4 smem16[];
+    __shared__ uint32_t word16[SCM_THREADS / 64];
+    uint4 *planes = smem16;                                         // [3][r/32][4][NB]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lm = lane & 15, lq = lane >> 4;
+    const int i0 = blockIdx.x * SC_SLAB + wave * 16;
+    const int nkb = r / 32;
+    SVDP_STAMP(1, 0);
+
+    uint4 q[SCM_KB];
+    const bf16 *qrow = Q + (size_t)(i0 + lm) * r + lq * 8;
+#pragma unroll
+    for (int kb = 0; kb < SCM_KB; ++kb)
+        if (kb < nkb) q[kb] = load_raw(qrow + kb * 32);
+    const float4 bs = *reinterpret_cast<const float4 *>(bias + i0 + lq * 4);
+
+    // t for (token b, columns 8g .. 8g+7): sum of the partials in order, then the three terms
+    const int ngr = r / 8;
+    for (int u = tid; u < NB * ngr; u += SCM_THREADS) {
+        const int b = u / ngr, g = u % ngr;
+        float t[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = 0.f;
+        const float4 *tp = reinterpret_cast<const float4 *>(tpart + (size_t)b * r + (size_t)g * 8);
+        const size_t stride4 = (size_t)NB * r / 4;
+#pragma unroll 4
+        for (int p = 0; p < nt; ++p) {
+            const float4 a = tp[p * stride4], c = tp[p * stride4 + 1];
+            t[0] += a.x; t[1] += a.y; t[2] += a.z; t[3] += a.w;
+            t[4] += c.x; t[5] += c.y; t[6] += c.z; t[7] += c.w;
+        }
+        uint32_t pl[3][8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t hi = bf16_rne_bits(t[e]);
+            const float r1 = t[e] - __uint_as_float(hi << 16);
+            const uint32_t mid = bf16_rne_bits(r1);
+            const float r2 = r1 - __uint_as_float(mid << 16);
+            pl[0][e] = hi; pl[1][e] = mid; pl[2][e] = bf16_rne_bits(r2);
+        }
+        const int slot = ((g >> 2) * 4 + (g & 3)) * NB + b;
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+            planes[(size_t)p * nkb * 4 * NB + slot] =
+                make_uint4(pl[p][0] | (pl[p][1] << 16), pl[p][2] | (pl[p][3] << 16), pl[p][4] | (pl[p][5] << 16),
+                           pl[p][6] | (pl[p][7] << 16));
+    }
+    __syncthreads();
+    SVDP_STAMP(1, 1);
+
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const int tb = lm & (NB - 1);
+#pragma unroll
+    for (int kb = 0; kb < SCM_KB; ++kb) {
+        if (kb < nkb) {
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+                acc = mfma_bf16(q[kb], planes[(size_t)p * nkb * 4 * NB + (kb * 4 + lq) * NB + tb], acc);
+        }
+    }
+    // the lane holds rows i0 + 4*lq .. +3 for token lm
+    const float sv[4] = {acc[0] + bs.x, acc[1] + bs.y, acc[2] + bs.z, acc[3] + bs.w};
+    if (s_out != nullptr && lm < B) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s_out[(size_t)lm * D + i0 + lq * 4 + i] = sv[i];
+    }
+    if (mask_out != nullptr) {
+        uint32_t w16 = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint64_t on = __ballot(lm < B && sv[i] > 0.f);
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq)
+                if ((on >> (16 * qq)) & 0xffffull) w16 |= 1u << (4 * qq + i);
+        }
+        if (lane == 0) word16[wave] = w16;
+        __syncthreads();
+        if (tid == 0)
+            mask_out[blockIdx.x] = (uint64_t)word16[0] | ((uint64_t)word16[1] << 16) | ((uint64_t)word16[2] << 32) |
+                                   ((uint64_t)word16[3] << 48);
+    }
+    SVDP_STAMP(1, 2);
 }
 
 }   // namespace svdp

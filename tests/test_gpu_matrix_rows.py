@@ -1,6 +1,6 @@
-"""GPU parity of the row kernel on the matrix cores (svdp_set_rows_engine) against
-the CPU oracle: every entry point that runs it, on seeded random layers whose row
-chunks span several 16-row tiles with ragged ends, for every batch size."""
+"""GPU parity of the kernels on the matrix cores (svdp_set_engine) against the CPU
+oracle: every entry point that runs them, on seeded random layers whose row chunks
+span several 16-row tiles with ragged ends, for every batch size and predictor rank."""
 import numpy as np
 import pytest
 
@@ -18,7 +18,7 @@ def env(oracle):
     assert torch.cuda.is_available(), "these tests need a GPU"
     binding.lib()
     yield binding, torch, oracle
-    binding.set_rows_engine(binding.ROWS_AUTO)
+    binding.set_engine(binding.ENGINE_AUTO)
 
 
 class RandomLayer:
@@ -54,8 +54,8 @@ def test_matrix_engine_every_entry_point(env, shape):
     f = c.f
     s_or = oracle.predict(f["P"], f["Q"], c.b, c.X)
     results = {}
-    for engine in (binding.ROWS_MATRIX, binding.ROWS_VECTOR):
-        binding.set_rows_engine(engine)
+    for engine in (binding.ENGINE_MATRIX, binding.ENGINE_VECTOR):
+        binding.set_engine(engine)
         # the whole step
         mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
         idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
@@ -81,11 +81,11 @@ def test_matrix_engine_every_entry_point(env, shape):
                        slack=parity.fp32_forward_bound(f, c.X, lst2))
         results[engine] = (lst, y.cpu().numpy(), yd.cpu().numpy())
     # the two engines: same list, y equal to fp32 rounding
-    assert np.array_equal(results[binding.ROWS_MATRIX][0], results[binding.ROWS_VECTOR][0])
+    assert np.array_equal(results[binding.ENGINE_MATRIX][0], results[binding.ENGINE_VECTOR][0])
     for k in (1, 2):
-        a, b = results[binding.ROWS_MATRIX][k].astype(np.float64), results[binding.ROWS_VECTOR][k].astype(np.float64)
+        a, b = results[binding.ENGINE_MATRIX][k].astype(np.float64), results[binding.ENGINE_VECTOR][k].astype(np.float64)
         assert np.linalg.norm(a - b) <= 2e-5 * max(np.linalg.norm(b), 1e-30)
-    binding.set_rows_engine(binding.ROWS_AUTO)
+    binding.set_engine(binding.ENGINE_AUTO)
 
 
 @pytest.mark.parametrize("shape", SHAPES[1:4])
@@ -100,7 +100,7 @@ def test_matrix_engine_arbitrary_lists(env, shape):
              np.sort(rng.choice(D, 255, replace=False)).astype(np.int32),          # fewer rows than blocks
              np.sort(rng.choice(D, 257, replace=False)).astype(np.int32),
              rng.permutation(D)[: D // 7].astype(np.int32)]                        # unsorted lists are allowed
-    binding.set_rows_engine(binding.ROWS_MATRIX)
+    binding.set_engine(binding.ENGINE_MATRIX)
     try:
         for Bq in (1, 2, 3, 4, 8):
             for lst in lists:
@@ -113,7 +113,41 @@ def test_matrix_engine_arbitrary_lists(env, shape):
                 if lst.size == 0:
                     assert not y.any()
     finally:
-        binding.set_rows_engine(binding.ROWS_AUTO)
+        binding.set_engine(binding.ENGINE_AUTO)
+
+
+# (d, D, r, B): ranks the score kernel on the matrix cores takes (multiples of 32 up to 512) and two it does not
+SCORE_SHAPES = [(256, 1024, 32, 1), (512, 2048, 128, 8), (264, 640, 256, 5), (512, 4096, 320, 3), (128, 832, 512, 8),
+                (128, 256, 544, 4), (96, 192, 48, 2), (1024, 3072, 256, 7)]
+
+
+@pytest.mark.parametrize("shape", SCORE_SHAPES)
+def test_matrix_engine_scores(env, shape):
+    """svdp_predict and the mask of svdp_ffn_step with the score kernel on the matrix cores."""
+    binding, torch, oracle = env
+    d, D, r, B = shape
+    c = RandomLayer(binding, torch, 31 + r, d, D, r, B)
+    f = c.f
+    s_or = oracle.predict(f["P"], f["Q"], c.b, c.X)
+    binding.set_engine(binding.ENGINE_MATRIX)
+    try:
+        for Bq in sorted({1, B}):
+            s = binding.predict(c.dev, c.Xd[:Bq]).cpu().numpy().astype(np.float64)
+            assert s.shape == (Bq, D)
+            assert np.all(np.abs(s - s_or[:Bq]) <= 2e-5 * np.abs(s_or[:Bq]).max(axis=1, keepdims=True))
+            mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+            idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+            nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+            y = binding.ffn_step(c.dev, c.Xd[:Bq], mask=mask, idx=idx, nnz=nnz)
+            lst = parity.check_mask_and_idx(s_or[:Bq], mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+            y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X[:Bq], lst)
+            parity.check_y(y.cpu().numpy(), y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X[:Bq], lst))
+            # svdp_compact on the materialised scores gives the step's list
+            m2, i2, n2 = binding.compact(binding.predict(c.dev, c.Xd[:Bq]))
+            assert torch.equal(m2, mask) and n2.item() == nnz.item()
+            assert torch.equal(i2[: nnz.item()], idx[: nnz.item()])
+    finally:
+        binding.set_engine(binding.ENGINE_AUTO)
 
 
 def test_engine_selection_and_determinism(env):
@@ -125,24 +159,24 @@ def test_engine_selection_and_determinism(env):
     c = RandomLayer(binding, torch, 11, 1024, 8704, 32, 8)
 
     def run(engine, B, dev=None):
-        binding.set_rows_engine(engine)
+        binding.set_engine(engine)
         y = binding.ffn_step(dev or c.dev, c.Xd[:B]).clone()
-        binding.set_rows_engine(binding.ROWS_AUTO)
+        binding.set_engine(binding.ENGINE_AUTO)
         return y
 
     for B in (1, 2, 3, 4, 5, 8):
-        ym, yv, ya = run(binding.ROWS_MATRIX, B), run(binding.ROWS_VECTOR, B), run(binding.ROWS_AUTO, B)
-        assert torch.equal(ym, run(binding.ROWS_MATRIX, B)) and torch.equal(yv, run(binding.ROWS_VECTOR, B))
+        ym, yv, ya = run(binding.ENGINE_MATRIX, B), run(binding.ENGINE_VECTOR, B), run(binding.ENGINE_AUTO, B)
+        assert torch.equal(ym, run(binding.ENGINE_MATRIX, B)) and torch.equal(yv, run(binding.ENGINE_VECTOR, B))
         assert not torch.equal(ym, yv)
         assert torch.equal(ya, ym if B >= 5 else yv)
     # re-validation: vector kernel under every setting
     dv = c.dev.with_flags(binding.FLAG_REVALIDATE)
-    assert torch.equal(run(binding.ROWS_MATRIX, 8, dv), run(binding.ROWS_VECTOR, 8, dv))
+    assert torch.equal(run(binding.ENGINE_MATRIX, 8, dv), run(binding.ENGINE_VECTOR, 8, dv))
     # d = 520: not a multiple of 512
     c2 = RandomLayer(binding, torch, 12, 520, 4160, 16, 8)
-    binding.set_rows_engine(binding.ROWS_MATRIX)
+    binding.set_engine(binding.ENGINE_MATRIX)
     y1 = binding.ffn_step(c2.dev, c2.Xd).clone()
-    binding.set_rows_engine(binding.ROWS_VECTOR)
+    binding.set_engine(binding.ENGINE_VECTOR)
     y2 = binding.ffn_step(c2.dev, c2.Xd).clone()
-    binding.set_rows_engine(binding.ROWS_AUTO)
+    binding.set_engine(binding.ENGINE_AUTO)
     assert torch.equal(y1, y2)
