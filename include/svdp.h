@@ -190,6 +190,30 @@ svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift,
                             int32_t d, int32_t dtype, float eps, void *x_next,
                             void *stream);
 
+/* ---- offline build: greedy bias calibration (Alg. 2; App. A "Greedy threshold selection") ----
+ *
+ * svdp_calib_bias runs Alg. 2 from its sort onward on given statistics of a calibration set:
+ *   w [D][T] fp32  damage weights  |ReLU(W_gate[i,:] x_t) (W_up[i,:] x_t)|^2 ||W_down[:, i]||^2
+ *   s [D][T] fp32  proxy scores    (A B x_t)_i  = the predictor's scores without bias
+ * (row i = neuron i, column t = sample t; both device, read only; no NaN).
+ * Per neuron the samples are sorted by score (equal scores keep sample order), the pointer starts at
+ * the first positive weight (at T if there is none) with tau = the score there, and the greedy loop
+ * advances the neuron whose next `eta` samples cost least (fp32 sum, left to right; smallest index
+ * among equal costs; pointer update k <- min(k + eta, T)) until at least `need` of the D*T
+ * (neuron, sample) pairs satisfy s <= tau, or no step is left.  For a sparsity level sp of Alg. 2,
+ * need = the smallest integer >= sp*D*T.
+ * Outputs (device): b [D] fp32 = -tau; k [D] int32 (nullable) the final pointers (counts, 1..T);
+ * steps [1] int32 (nullable) the number of greedy steps taken; kendall [D] fp32 (nullable) App. A's
+ * check 1 - K_d / (M (M-1)) of the eta-step sums' order, M = T / eta.
+ * The result equals the sequential priority-queue loop exactly (integers and bit patterns).
+ * Limits: 1 <= T <= 4096, eta >= 1, D >= 1; otherwise SVDP_ERR_UNSUPPORTED / SVDP_ERR_INVALID_ARG.
+ * ws: device, 256-byte aligned, >= svdp_calib_workspace_bytes(D, T, eta) (0 for invalid sizes).
+ * Asynchronous on `stream`, no allocation, no host read-back.                                     */
+size_t svdp_calib_workspace_bytes(int32_t D, int32_t T, int32_t eta);
+svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
+                            float *b, int32_t *k, int32_t *steps, float *kendall,
+                            void *ws, size_t ws_bytes, void *stream);
+
 /* Static string for a status code.  Never NULL. */
 const char *svdp_status_string(svdp_status st);
 

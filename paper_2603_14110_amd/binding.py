@@ -7,6 +7,7 @@ or eager fallback: if the library has not been built, ``lib()`` raises.
 from __future__ import annotations
 
 import ctypes
+import math
 import os
 from typing import Optional, Tuple
 
@@ -23,7 +24,7 @@ MAX_BATCH = 8
 EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
     "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version", "svdp_set_step_mode",
-    "svdp_step_timeouts", "svdp_active_rows", "svdp_set_engine",
+    "svdp_step_timeouts", "svdp_active_rows", "svdp_set_engine", "svdp_calib_workspace_bytes", "svdp_calib_bias",
 ]
 
 
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
     L.svdp_version.restype = ctypes.c_char_p
     L.svdp_set_step_mode.argtypes = [i32, i32]
     L.svdp_set_step_mode.restype = None
+    L.svdp_calib_workspace_bytes.argtypes = [i32, i32, i32]
+    L.svdp_calib_workspace_bytes.restype = ctypes.c_size_t
+    L.svdp_calib_bias.argtypes = [vp, vp, i32, i32, i32, ctypes.c_int64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.svdp_calib_bias.restype = ctypes.c_int
     L.svdp_set_engine.argtypes = [i32]
     L.svdp_set_engine.restype = None
     L.svdp_step_timeouts.argtypes = [ctypes.POINTER(ctypes.c_int32)]
@@ -249,6 +254,29 @@ ENGINE_AUTO, ENGINE_VECTOR, ENGINE_MATRIX = 0, 1, 2
 
 def set_engine(engine: int) -> None:
     lib().svdp_set_engine(int(engine))
+
+
+def calib_need(sparsity: float, D: int, T: int) -> int:
+    """Number of (neuron, sample) pairs Alg. 2's loop has to reach for a sparsity level."""
+    return min(max(int(math.ceil(sparsity * D * T)), 0), D * T)
+
+
+def calib_bias(w: torch.Tensor, s: torch.Tensor, eta: int, need: int, want_kendall: bool = False):
+    """Greedy bias calibration on device tensors w, s of shape [D][T] (fp32).
+    Returns (b [D] fp32, k [D] int32, steps [1] int32, kendall [D] fp32 or None), all on the device."""
+    assert w.shape == s.shape and w.dim() == 2 and w.dtype == torch.float32 and s.dtype == torch.float32
+    D, T = w.shape
+    nbytes = lib().svdp_calib_workspace_bytes(D, T, int(eta))
+    if nbytes == 0:
+        raise SvdpError(f"svdp_calib_bias: unsupported sizes D={D} T={T} eta={eta}")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    b = torch.empty(D, dtype=torch.float32, device=w.device)
+    k = torch.empty(D, dtype=torch.int32, device=w.device)
+    steps = torch.empty(1, dtype=torch.int32, device=w.device)
+    kend = torch.empty(D, dtype=torch.float32, device=w.device) if want_kendall else None
+    _check(lib().svdp_calib_bias(_ptr(w), _ptr(s), D, T, int(eta), int(need), _ptr(b), _ptr(k), _ptr(steps),
+                                 _ptr(kend), _ptr(ws), ws.numel(), _stream()), "svdp_calib_bias")
+    return b, k, steps, kend
 
 
 def step_timeouts() -> int:

@@ -7,6 +7,7 @@
 #include "svdp_kernels.h"
 #include "svdp_fused.h"
 #include "svdp_rows_mfma.h"
+#include "svdp_calib.h"
 
 #include <atomic>
 #include <mutex>
@@ -580,6 +581,46 @@ const char *svdp_status_string(svdp_status st)
     case SVDP_ERR_HIP: return "HIP runtime error";
     }
     return "unknown status";
+}
+
+size_t svdp_calib_workspace_bytes(int32_t D, int32_t T, int32_t eta)
+{
+    if (D < 1 || T < 1 || T > CAL_MAX_T || eta < 1) return 0;
+    const size_t MS = ((size_t)T + eta - 1) / eta;
+    return align_up((size_t)D * MS * 4) + 2 * align_up((size_t)D * (MS + 1) * 4) + align_up((size_t)D * 4);
+}
+
+svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
+                            float *b, int32_t *k, int32_t *steps, float *kendall, void *ws, size_t ws_bytes,
+                            void *stream)
+{
+    if (w == nullptr || s == nullptr || b == nullptr || D < 1 || T < 1 || eta < 1 || need < 0)
+        return SVDP_ERR_INVALID_ARG;
+    if (T > CAL_MAX_T) return SVDP_ERR_UNSUPPORTED;
+    const size_t bytes = svdp_calib_workspace_bytes(D, T, eta);
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1)) || ws_bytes < bytes) return SVDP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int MS = (T + eta - 1) / eta;
+    char *p = static_cast<char *>(ws);
+    float *key = reinterpret_cast<float *>(p);
+    p += align_up((size_t)D * MS * 4);
+    int32_t *drop = reinterpret_cast<int32_t *>(p);
+    p += align_up((size_t)D * (MS + 1) * 4);
+    float *tauc = reinterpret_cast<float *>(p);
+    p += align_up((size_t)D * (MS + 1) * 4);
+    int32_t *k0 = reinterpret_cast<int32_t *>(p);
+    int n2 = 1;
+    while (n2 < T) n2 <<= 1;
+    const size_t lds = (size_t)n2 * 8 + (size_t)T * 8 + (size_t)(MS + 1) * 8;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_calib_sort, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_calib_sort, dim3(D), dim3(CAL_THREADS), lds, st, w, s, T, n2, eta, MS, key, drop, tauc, k0,
+                       kendall);
+    svdp_status e = hip_status(hipSuccess);
+    if (e != SVDP_OK) return e;
+    hipLaunchKernelGGL(k_calib_select, dim3(1), dim3(SEL_THREADS), 0, st, key, drop, tauc, k0, D, T, eta, MS,
+                       (long long)need, b, k, steps);
+    return hip_status(hipSuccess);
 }
 
 const char *svdp_version(void) { return "0.2"; }
