@@ -210,6 +210,15 @@ svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift,
  * ws: device, 256-byte aligned, >= svdp_calib_workspace_bytes(D, T, eta) (0 for invalid sizes).
  * Asynchronous on `stream`, no allocation, no host read-back.                                     */
 size_t svdp_calib_workspace_bytes(int32_t D, int32_t T, int32_t eta);
+
+/* The statistics svdp_calib_bias consumes, for T calibration tokens X [T][d] (device, in the
+ * layer's storage type): w [D][T] and s [D][T] as defined above, with A B x evaluated the way
+ * the runtime predictor does, (x P) Q^T in fp32 (the layer's bias b is not used).  Dense
+ * contractions on the matrix cores.  bf16 storage only (SVDP_ERR_UNSUPPORTED otherwise).
+ * ws: device, 256-byte aligned, >= svdp_calib_stats_workspace_bytes(layer, T).                     */
+size_t svdp_calib_stats_workspace_bytes(const svdp_layer *layer, int32_t T);
+svdp_status svdp_calib_stats(const svdp_layer *layer, const void *X, int32_t T, float *w, float *s,
+                             void *ws, size_t ws_bytes, void *stream);
 svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
                             float *b, int32_t *k, int32_t *steps, float *kendall,
                             void *ws, size_t ws_bytes, void *stream);

@@ -25,6 +25,7 @@ EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
     "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version", "svdp_set_step_mode",
     "svdp_step_timeouts", "svdp_active_rows", "svdp_set_engine", "svdp_calib_workspace_bytes", "svdp_calib_bias",
+    "svdp_calib_stats_workspace_bytes", "svdp_calib_stats",
 ]
 
 
@@ -77,6 +78,10 @@ def lib() -> ctypes.CDLL:
     L.svdp_calib_workspace_bytes.restype = ctypes.c_size_t
     L.svdp_calib_bias.argtypes = [vp, vp, i32, i32, i32, ctypes.c_int64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.svdp_calib_bias.restype = ctypes.c_int
+    L.svdp_calib_stats_workspace_bytes.argtypes = [lp, i32]
+    L.svdp_calib_stats_workspace_bytes.restype = ctypes.c_size_t
+    L.svdp_calib_stats.argtypes = [lp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
+    L.svdp_calib_stats.restype = ctypes.c_int
     L.svdp_set_engine.argtypes = [i32]
     L.svdp_set_engine.restype = None
     L.svdp_step_timeouts.argtypes = [ctypes.POINTER(ctypes.c_int32)]
@@ -254,6 +259,22 @@ ENGINE_AUTO, ENGINE_VECTOR, ENGINE_MATRIX = 0, 1, 2
 
 def set_engine(engine: int) -> None:
     lib().svdp_set_engine(int(engine))
+
+
+def calib_stats(layer: "DeviceLayer", X: torch.Tensor):
+    """Damage weights and proxy scores of T calibration tokens X [T][d]: two device tensors [D][T] fp32."""
+    assert X.dim() == 2 and X.is_cuda and X.is_contiguous()
+    T = X.shape[0]
+    D = layer.c.D
+    nbytes = lib().svdp_calib_stats_workspace_bytes(ctypes.byref(layer.c), T)
+    if nbytes == 0:
+        raise SvdpError("svdp_calib_stats: unsupported layer (bf16 storage only) or T < 1")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=X.device)
+    w = torch.empty((D, T), dtype=torch.float32, device=X.device)
+    s = torch.empty((D, T), dtype=torch.float32, device=X.device)
+    _check(lib().svdp_calib_stats(ctypes.byref(layer.c), _ptr(X), T, _ptr(w), _ptr(s), _ptr(ws), ws.numel(),
+                                  _stream()), "svdp_calib_stats")
+    return w, s
 
 
 def calib_need(sparsity: float, D: int, T: int) -> int:

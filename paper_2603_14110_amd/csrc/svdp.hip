@@ -8,6 +8,7 @@
 #include "svdp_fused.h"
 #include "svdp_rows_mfma.h"
 #include "svdp_calib.h"
+#include "svdp_calib_stats.h"
 
 #include <atomic>
 #include <mutex>
@@ -620,6 +621,51 @@ svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T
     if (e != SVDP_OK) return e;
     hipLaunchKernelGGL(k_calib_select, dim3(1), dim3(SEL_THREADS), 0, st, key, drop, tauc, k0, D, T, eta, MS,
                        (long long)need, b, k, steps);
+    return hip_status(hipSuccess);
+}
+
+size_t svdp_calib_stats_workspace_bytes(const svdp_layer *layer, int32_t T)
+{
+    if (check_layer(layer, true, true) != SVDP_OK || layer->wdtype != SVDP_BF16 || T < 1) return 0;
+    return align_up((size_t)layer->r * layer->d * 2) + align_up((size_t)layer->D * 4) +
+           align_up((size_t)T * 3 * layer->r * 2);
+}
+
+svdp_status svdp_calib_stats(const svdp_layer *layer, const void *X, int32_t T, float *w, float *s, void *ws,
+                             size_t ws_bytes, void *stream)
+{
+    svdp_status e = check_layer(layer, true, true);
+    if (e != SVDP_OK) return e;
+    if (X == nullptr || w == nullptr || s == nullptr || T < 1) return SVDP_ERR_INVALID_ARG;
+    if (layer->wdtype != SVDP_BF16) return SVDP_ERR_UNSUPPORTED;
+    const size_t bytes = svdp_calib_stats_workspace_bytes(layer, T);
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1)) || ws_bytes < bytes) return SVDP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int d = layer->d, D = layer->D, r = layer->r;
+    char *p = static_cast<char *>(ws);
+    bf16 *Pt = reinterpret_cast<bf16 *>(p);                      // [r][d]
+    p += align_up((size_t)r * d * 2);
+    float *cn = reinterpret_cast<float *>(p);                    // [D] squared column norms of W_down
+    p += align_up((size_t)D * 4);
+    uint16_t *tp = reinterpret_cast<uint16_t *>(p);              // [T][3r]: t = x P as three bf16 terms
+    const bf16 *Wg = static_cast<const bf16 *>(layer->W_gate), *Wu = static_cast<const bf16 *>(layer->W_up);
+    const bf16 *Xb = static_cast<const bf16 *>(X);
+    auto tiles = [](int n, int b) { return (n + b - 1) / b; };
+
+    hipLaunchKernelGGL(k_row_norm2, dim3(tiles(D, 4)), dim3(256), 0, st, static_cast<const bf16 *>(layer->W_downT), D, d,
+                       cn);
+    hipLaunchKernelGGL(k_transpose16, dim3(tiles(r, 32), tiles(d, 32)), dim3(256), 0, st,
+                       static_cast<const uint16_t *>(layer->P), d, r, reinterpret_cast<uint16_t *>(Pt));
+    // w = (ReLU(W_gate X^T) * (W_up X^T))^2 * cn
+    hipLaunchKernelGGL((k_gemm_nt<2, EPI_DAMAGE>), dim3(tiles(T, GM_BN), tiles(D, GM_BM)), dim3(GM_THREADS), 0, st, Wg,
+                       Wu, d, d, Xb, d, D, T, d, cn, w, nullptr, T);
+    // t = X P, split
+    hipLaunchKernelGGL((k_gemm_nt<1, EPI_SPLIT3>), dim3(tiles(r, GM_BN), tiles(T, GM_BM)), dim3(GM_THREADS), 0, st, Xb,
+                       nullptr, d, d, Pt, d, T, r, d, nullptr, nullptr, tp, 3 * r);
+    // s = Q t^T over the three terms
+    hipLaunchKernelGGL((k_gemm_nt<1, EPI_PLAIN>), dim3(tiles(T, GM_BN), tiles(D, GM_BM)), dim3(GM_THREADS), 0, st,
+                       static_cast<const bf16 *>(layer->Q), nullptr, r, r, reinterpret_cast<const bf16 *>(tp), 3 * r, D,
+                       T, 3 * r, nullptr, s, nullptr, T);
     return hip_status(hipSuccess);
 }
 

@@ -110,3 +110,84 @@ def test_validation(env):
     w = torch.zeros(4, 8, device="cuda")
     with pytest.raises(binding.SvdpError):
         binding.calib_bias(w, w.clone(), 0, 3)
+
+
+# ------------------------------------------------------------ statistics (svdp_calib_stats) -----
+def _bf16_layer(env, seed, d, D, r, T):
+    binding, torch, calib = env
+    from paper_2603_14110_amd import synth
+
+    rng = np.random.default_rng(seed)
+    st = lambda a: synth.to_storage(a, "bf16")
+    Wg, Wu, Wd = (st(rng.standard_normal((D, d)) / np.sqrt(d)) for _ in range(3))
+    P, Q = st(rng.standard_normal((d, r)) / np.sqrt(d)), st(rng.standard_normal((D, r)))
+    X = st(rng.standard_normal((T, d)) + 0.5)
+    f = {k: synth.storage_to_f32(v, "bf16") for k, v in dict(W_gate=Wg, W_up=Wu, W_downT=Wd, P=P, Q=Q, X=X).items()}
+    dev = binding.DeviceLayer(*(binding.to_device(a, "bf16") for a in (P, Q)), torch.zeros(D, device="cuda"),
+                              *(binding.to_device(a, "bf16") for a in (Wg, Wu, Wd)))
+    return f, dev, binding.to_device(X, "bf16")
+
+
+STAT_SHAPES = [(64, 128, 32, 50), (264, 640, 40, 130), (1024, 2560, 72, 300), (512, 4160, 256, 257), (72, 64, 8, 1)]
+
+
+@pytest.mark.parametrize("shape", STAT_SHAPES)
+def test_stats_against_the_oracle(env, shape):
+    binding, torch, calib = env
+    d, D, r, T = shape
+    f, dev, Xd = _bf16_layer(env, 100 + d, d, D, r, T)
+    w, s = binding.calib_stats(dev, Xd)
+    torch.cuda.synchronize()
+    w, s = w.cpu().numpy().astype(np.float64), s.cpu().numpy().astype(np.float64)
+    assert w.shape == (D, T) and s.shape == (D, T)
+    # proxy scores: A = Q, B = P^T; the tolerance of the runtime predictor's scores
+    s_or = calib.proxy_scores(f["Q"], f["P"].T, f["X"])
+    assert np.all(np.abs(s - s_or) <= 2e-5 * np.abs(s_or).max(axis=0, keepdims=True))
+    # damage weights: forward error bound of fp32 accumulation of exact products, carried through z^2 * norm
+    w_or = calib.damage_weights(f["W_gate"], f["W_up"], f["W_downT"], f["X"])
+    Xa = np.abs(f["X"].astype(np.float64))
+    gam = d * 2.0 ** -24 / 4
+    eg, eu = gam * (np.abs(f["W_gate"]).astype(np.float64) @ Xa.T), gam * (np.abs(f["W_up"]).astype(np.float64) @ Xa.T)
+    g = f["W_gate"].astype(np.float64) @ f["X"].astype(np.float64).T
+    u = f["W_up"].astype(np.float64) @ f["X"].astype(np.float64).T
+    cn = np.sum(f["W_downT"].astype(np.float64) ** 2, axis=1)[:, None]
+    z = np.maximum(g, 0) * u
+    dz = eg * np.abs(u) + eu * np.maximum(g, 0) + eg * eu
+    bound = cn * (2 * np.abs(z) * dz + dz * dz) * 1.01 + 1e-5 * w_or
+    assert np.all(np.abs(w - w_or) <= bound), float(np.max(np.abs(w - w_or) - bound))
+    assert np.all(w >= 0) and np.all((w == 0) | (g > -eg))
+
+
+def test_statistics_then_calibration_end_to_end(env):
+    """The two GPU calls chained, against the oracle's pipeline on its own fp64 statistics: the pointers may
+    differ where costs agree to rounding, the achieved sparsity and the loss may not."""
+    binding, torch, calib = env
+    d, D, r, T, eta = 256, 1024, 32, 512, 8
+    f, dev, Xd = _bf16_layer(env, 9, d, D, r, T)
+    w, s = binding.calib_stats(dev, Xd)
+    need = binding.calib_need(0.85, D, T)
+    b, k, steps, _ = binding.calib_bias(w, s, eta, need)
+    torch.cuda.synchronize()
+    w_or = calib.damage_weights(f["W_gate"], f["W_up"], f["W_downT"], f["X"])
+    s_or = calib.proxy_scores(f["Q"], f["P"].T, f["X"])
+    ref = calib.greedy_bias(w_or, s_or, need, eta)
+    tau = -b.cpu().numpy()
+    got_cnt = int(np.sum(s_or.astype(np.float32) <= tau[:, None]))
+    assert abs(got_cnt - ref["count"]) <= 2e-3 * D * T
+    l_gpu, l_ref = calib.calibration_loss(w_or, s_or.astype(np.float32), tau), calib.calibration_loss(
+        w_or, s_or.astype(np.float32), ref["tau"])
+    assert abs(l_gpu - l_ref) <= 1e-2 * l_ref
+    assert np.mean(k.cpu().numpy() == ref["k"]) > 0.9
+    # and exactly the oracle's loop on the GPU's own statistics
+    ref2 = calib.greedy_bias(w.cpu().numpy(), s.cpu().numpy(), need, eta)
+    assert np.array_equal(k.cpu().numpy(), ref2["k"]) and steps.item() == ref2["steps"]
+
+
+def test_stats_reject_fp32_layers(env):
+    binding, torch, calib = env
+    from paper_2603_14110_amd import synth
+
+    L = synth.make_layer(synth.workload("tiny"))
+    dev = binding.DeviceLayer.from_synth(L)
+    with pytest.raises(binding.SvdpError):
+        binding.calib_stats(dev, binding.to_device(synth.timed_tokens(L, 4), "f32"))
