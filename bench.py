@@ -49,6 +49,11 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--table4", action="store_true",
                     help="instead of the step benchmark: FFN-only speed-up at fixed sparsity on the paper's three shapes")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="time the offline bias calibration (Alg. 2) of the 7B-shaped layer instead of the decode step")
+    ap.add_argument("--calib-tokens", type=int, default=2048)
+    ap.add_argument("--calib-eta", type=int, default=16)
+    ap.add_argument("--calib-sparsity", type=float, default=0.9)
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
@@ -263,6 +268,77 @@ def table4(a):
                                "cold weights (8 copies)", "rows": rows}))
 
 
+def calibrate(a):
+    """Offline bias calibration (Alg. 2) of one layer on the GPU: statistics of T calibration tokens
+    (svdp_calib_stats, MFMA contractions), then the greedy selection (svdp_calib_bias).  One JSON line."""
+    import time
+
+    import numpy as np
+    import torch
+
+    from paper_2603_14110_amd import binding, synth
+
+    L = synth.load_or_make(synth.workload(a.workload if a.workload in ("7b", "13b", "mistral") else "7b"))
+    sp = L.spec
+    dev = binding.DeviceLayer.from_synth(L)
+    T, eta = a.calib_tokens, a.calib_eta
+    Xc = synth.make_tokens(sp, L.u, T, 1)                                         # the generator's calibration stream
+    Xd = binding.to_device(Xc, sp.dtype)
+    need = binding.calib_need(a.calib_sparsity, sp.D, T)
+    st = torch.cuda.Stream()
+
+    def timed(fn, reps):
+        with torch.cuda.stream(st):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for _ in range(reps):
+                out = fn()
+            e1.record(st)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps, out
+
+    ms_stats, (w, s) = timed(lambda: binding.calib_stats(dev, Xd), 5)
+    ms_bias, (b, k, steps, _) = timed(lambda: binding.calib_bias(w, s, eta, need), 3)
+    ms_bias_k, _ = timed(lambda: binding.calib_bias(w, s, eta, need, want_kendall=True), 3)
+    # the dominant contraction: gate and up against the tokens
+    flops = 2.0 * 2.0 * sp.D * T * sp.d
+    total_flops = flops + 2.0 * T * sp.r * sp.d + 2.0 * 3 * sp.D * T * sp.r
+    tflops = total_flops / (ms_stats * 1e-3) / 1e12
+    # what the calibrated bias does on the timed tokens, against the generator's recall-based bias
+    Xt = binding.to_device(synth.timed_tokens(L, 256), sp.dtype)
+    w_t, s_t = binding.calib_stats(dev, Xt)
+    act = (w_t > 0)
+    on_new, on_old = s_t + b[:, None] > 0, s_t + dev.tensors["b"][:, None] > 0
+    summ = lambda on: {"density": float(on.float().mean()), "recall_of_active": float((on & act).sum() / act.sum()),
+                       "lost_damage_fraction": float((w_t * (~on)).sum() / w_t.sum())}
+    # CPU oracle: the same layer and tokens (numpy contractions, then the priority-queue loop in Python)
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import calib
+
+        f = {n: L.f32(n) for n in ("W_gate", "W_up", "W_downT", "Q")}
+        Xf = synth.storage_to_f32(Xc, sp.dtype)
+        t0 = time.perf_counter()
+        wo = calib.damage_weights(f["W_gate"], f["W_up"], f["W_downT"], Xf)
+        so = calib.proxy_scores(f["Q"], L.f32("P").T, Xf)
+        ref = calib.greedy_bias(wo, so, need, eta)
+        dt = time.perf_counter() - t0
+        cpu = {"value": dt * 1e3, "unit": "ms per layer", "cores": os.cpu_count(), "kind": "oracle",
+               "sample": f"the whole layer, {T} tokens, {ref['steps']} greedy steps"}
+    print(json.dumps({
+        "metric": "offline_bias_calibration_ms_per_layer", "value": ms_stats + ms_bias, "unit": "ms", "n_gpus": 1,
+        "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{sp.name} layer d={sp.d} D={sp.D} r={sp.r}, {T} calibration tokens, eta={eta}, "
+                               f"sparsity level {a.calib_sparsity}"},
+        "stats_ms": ms_stats, "bias_ms": ms_bias, "bias_with_kendall_ms": ms_bias_k, "greedy_steps": int(steps.item()),
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": 2500.0, "unit": "TFLOP/s", "frac": tflops / 2500.0,
+                     "traffic": None, "kernel": "svdp_calib_stats (k_gemm_nt x3 + row norms + transpose), bf16 MFMA"},
+        "on_256_decode_tokens": {"calibrated_bias": summ(on_new), "generator_bias": summ(on_old)},
+        "cpu_baseline": cpu}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -280,6 +356,9 @@ def main():
                              "matrix": binding.ENGINE_MATRIX}[a.engine])
     if a.table4:
         table4(a)
+        return
+    if a.calibrate:
+        calibrate(a)
         return
     r = (run_stack if a.workload == "stack" else run_layer)(a, torch, np, binding, cost, synth)
     if a.calib_copy_mb:

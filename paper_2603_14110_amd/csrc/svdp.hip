@@ -588,7 +588,8 @@ size_t svdp_calib_workspace_bytes(int32_t D, int32_t T, int32_t eta)
 {
     if (D < 1 || T < 1 || T > CAL_MAX_T || eta < 1) return 0;
     const size_t MS = ((size_t)T + eta - 1) / eta;
-    return align_up((size_t)D * MS * 4) + 2 * align_up((size_t)D * (MS + 1) * 4) + align_up((size_t)D * 4);
+    return align_up((size_t)D * MS * 4) + 2 * align_up((size_t)D * (MS + 1) * 4) + align_up((size_t)D * 4) +
+           align_up(sizeof(SelectState)) + align_up((size_t)SEL_BINS * 8);
 }
 
 svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
@@ -619,8 +620,23 @@ svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T
                        kendall);
     svdp_status e = hip_status(hipSuccess);
     if (e != SVDP_OK) return e;
-    hipLaunchKernelGGL(k_calib_select, dim3(1), dim3(SEL_THREADS), 0, st, key, drop, tauc, k0, D, T, eta, MS,
-                       (long long)need, b, k, steps);
+    p += align_up((size_t)D * 4);
+    SelectState *state = reinterpret_cast<SelectState *>(p);
+    p += align_up(sizeof(SelectState));
+    long long *hist = reinterpret_cast<long long *>(p);
+    const size_t items = (size_t)D * MS;
+    const int hb = (int)((items + 256 * 8 - 1) / (256 * 8) < 2048 ? (items + 256 * 8 - 1) / (256 * 8) : 2048);
+    hipLaunchKernelGGL(k_select_init, dim3(1), dim3(SEL_THREADS), 0, st, drop, D, MS, (long long)need, state, hist);
+    hipLaunchKernelGGL((k_select_hist<23, 8>), dim3(hb), dim3(256), 0, st, key, drop, D, MS, state, hist);
+    hipLaunchKernelGGL((k_select_pick<23, true>), dim3(1), dim3(64), 0, st, state, hist);
+    hipLaunchKernelGGL((k_select_hist<15, 8>), dim3(hb), dim3(256), 0, st, key, drop, D, MS, state, hist);
+    hipLaunchKernelGGL((k_select_pick<15, false>), dim3(1), dim3(64), 0, st, state, hist);
+    hipLaunchKernelGGL((k_select_hist<7, 8>), dim3(hb), dim3(256), 0, st, key, drop, D, MS, state, hist);
+    hipLaunchKernelGGL((k_select_pick<7, false>), dim3(1), dim3(64), 0, st, state, hist);
+    hipLaunchKernelGGL((k_select_hist<0, 7>), dim3(hb), dim3(256), 0, st, key, drop, D, MS, state, hist);
+    hipLaunchKernelGGL((k_select_pick<0, false>), dim3(1), dim3(64), 0, st, state, hist);
+    hipLaunchKernelGGL(k_select_finish, dim3(1), dim3(SEL_THREADS), 0, st, key, drop, tauc, k0, D, T, eta, MS, state, b,
+                       k, steps);
     return hip_status(hipSuccess);
 }
 

@@ -14,9 +14,11 @@
 //                  costs (fp32, left to right), their running maxima, and for
 //                  every step the number of dropped samples and the threshold
 //                  it would set; optionally the Kendall check of App. A.
-//   k_calib_select one block: bisection on the cost level at which the required
-//                  number of pairs is first reached, then the steps at exactly
-//                  that level in neuron order; writes b = -tau and the pointers.
+//   k_select_*     the cost level at which the required number of pairs is first
+//                  reached, by a radix select over the keys' bit patterns
+//                  (four digit passes, integer atomics); then one block takes
+//                  the steps at exactly that level in neuron order and writes
+//                  b = -tau and the pointers.
 // Integer results equal the sequential algorithm's bit for bit.
 #pragma once
 
@@ -161,94 +163,142 @@ __device__ __forceinline__ long long block_sum_i64(long long v, long long *red)
     if (lane == 0) red[wave] = v;
     __syncthreads();
     long long t = 0;
-    for (int q = 0; q < SEL_THREADS / 64; ++q) t += red[q];
+    for (int q = 0; q < (int)blockDim.x / 64; ++q) t += red[q];
     return t;
 }
 
-// Number of steps of neuron i whose key is <= level (keys are non-decreasing; +inf pads).
-__device__ __forceinline__ int steps_up_to(const float *__restrict__ key_i, int MS, float level)
+// Number of steps of a neuron whose key is <= level (INCLUSIVE) or < level (keys are non-decreasing; +inf pads).
+template <bool INCLUSIVE>
+__device__ __forceinline__ int steps_below(const float *__restrict__ key_i, int MS, float level)
 {
     int lo = 0, hi = MS;
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
-        if (key_i[mid] <= level) lo = mid + 1;
+        const float v = key_i[mid];
+        if (INCLUSIVE ? v <= level : v < level) lo = mid + 1;
         else hi = mid;
     }
     return lo;
 }
 
-__global__ __launch_bounds__(SEL_THREADS) void k_calib_select(const float *__restrict__ key,
-                                                              const int32_t *__restrict__ drop,
-                                                              const float *__restrict__ tauc,
-                                                              const int32_t *__restrict__ k0, int D, int T, int eta,
-                                                              int MS, long long need, float *__restrict__ b,
-                                                              int32_t *__restrict__ k_out, int32_t *__restrict__ steps)
+// The cost level at which the required number of pairs is first reached is found by a radix
+// select over the bit patterns of the (non-negative) keys, most significant digit first: the pairs a
+// step adds (its gain) are summed per digit value among the steps that match the digits found so
+// far, and the digit is where the running sum first covers what is still missing.  Integer atomics
+// only, so the result does not depend on the order of arrival.
+struct SelectState {
+    long long missing;       // pairs still to be found among steps at or above the current prefix
+    long long c0;            // pairs dropped before any step
+    uint32_t prefix;         // digits of the level found so far
+    int32_t reachable;       // 0: the start already meets the target, or all finite steps together do not
+    int32_t at_start;        // 1: the start already meets the target (no step is taken)
+};
+constexpr int SEL_BINS = 256;
+constexpr uint32_t SEL_TOP = 0x7f7fffffu;      // largest finite float: keys above it are padding
+
+__global__ __launch_bounds__(SEL_THREADS) void k_select_init(const int32_t *__restrict__ drop, int D, int MS,
+                                                             long long need, SelectState *__restrict__ st,
+                                                             long long *__restrict__ hist)
+{
+    __shared__ long long red[SEL_THREADS / 64];
+    long long c0 = 0;
+    for (int i = threadIdx.x; i < D; i += SEL_THREADS) c0 += drop[(size_t)i * (MS + 1)];
+    c0 = block_sum_i64(c0, red);
+    if (threadIdx.x < SEL_BINS) hist[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+        st->c0 = c0;
+        st->missing = need - c0;
+        st->prefix = 0u;
+        st->reachable = c0 < need ? 1 : 0;
+        st->at_start = c0 < need ? 0 : 1;
+    }
+}
+
+// hist[digit] += gain over the steps whose key matches the prefix above this digit.
+template <int SHIFT, int BITS>
+__global__ __launch_bounds__(256) void k_select_hist(const float *__restrict__ key, const int32_t *__restrict__ drop,
+                                                     int D, int MS, const SelectState *__restrict__ st,
+                                                     long long *__restrict__ hist)
+{
+    __shared__ long long lh[SEL_BINS];
+    if (st->reachable == 0) return;
+    const uint32_t prefix = st->prefix;
+    for (int q = threadIdx.x; q < SEL_BINS; q += 256) lh[q] = 0;
+    __syncthreads();
+    const size_t total = (size_t)D * MS;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+        const int i = (int)(e / MS), j = (int)(e % MS);
+        const uint32_t kb = __float_as_uint(key[e]);
+        if (kb > SEL_TOP) continue;
+        if (SHIFT + BITS < 31 && (kb >> (SHIFT + BITS)) != (prefix >> (SHIFT + BITS))) continue;
+        const int32_t *di = drop + (size_t)i * (MS + 1);
+        const long long gain = (long long)di[j + 1] - di[j];
+        if (gain != 0) atomicAdd(reinterpret_cast<unsigned long long *>(&lh[(kb >> SHIFT) & ((1u << BITS) - 1u)]),
+                                 (unsigned long long)gain);
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < SEL_BINS; q += 256)
+        if (lh[q] != 0) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[q]), (unsigned long long)lh[q]);
+}
+
+// Picks the digit, updates the state and clears the histogram for the next digit.
+template <int SHIFT, bool FIRST>
+__global__ __launch_bounds__(64) void k_select_pick(SelectState *__restrict__ st, long long *__restrict__ hist)
+{
+    if (threadIdx.x != 0) return;
+    if (st->reachable != 0) {
+        long long run = 0;
+        int digit = -1;
+        const long long missing = st->missing;
+        for (int q = 0; q < SEL_BINS; ++q) {
+            if (digit < 0 && run + hist[q] >= missing) {
+                digit = q;
+                break;
+            }
+            run += hist[q];
+        }
+        if (digit < 0) {
+            st->reachable = 0;                  // only on the first digit: every finite step together falls short
+        } else {
+            st->missing = missing - run;        // still to be found among the steps with this digit
+            st->prefix |= (uint32_t)digit << SHIFT;
+        }
+    }
+    for (int q = 0; q < SEL_BINS; ++q) hist[q] = 0;
+}
+
+// With the level known: steps strictly below it are all taken; those at the level in neuron order
+// until the missing pairs are found; writes b = -tau, the pointers and the number of steps.
+__global__ __launch_bounds__(SEL_THREADS) void k_select_finish(const float *__restrict__ key,
+                                                               const int32_t *__restrict__ drop,
+                                                               const float *__restrict__ tauc,
+                                                               const int32_t *__restrict__ k0, int D, int T, int eta,
+                                                               int MS, const SelectState *__restrict__ st,
+                                                               float *__restrict__ b, int32_t *__restrict__ k_out,
+                                                               int32_t *__restrict__ steps)
 {
     __shared__ long long red[SEL_THREADS / 64];
     __shared__ long long wave_tot[SEL_THREADS / 64];
     __shared__ int star;                                            // neuron at which the target is reached
-    __shared__ long long star_before;                               // pairs dropped before its steps at the level
+    __shared__ long long star_before;                               // pairs found before its steps at the level
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    auto count_at = [&](float level) -> long long {
-        long long c = 0;
-        for (int i = tid; i < D; i += SEL_THREADS)
-            c += drop[(size_t)i * (MS + 1) + steps_up_to(key + (size_t)i * MS, MS, level)];
-        return block_sum_i64(c, red);
-    };
-    long long c0 = 0;
-    for (int i = tid; i < D; i += SEL_THREADS) c0 += drop[(size_t)i * (MS + 1)];
-    c0 = block_sum_i64(c0, red);
-
-    // lowest cost level (as a bit pattern of a non-negative float) at which the target is reached
-    const uint32_t top = 0x7f7fffffu;                               // largest finite float
-    bool reachable = c0 < need && count_at(__uint_as_float(top)) >= need;
-    uint32_t level = top;
-    if (reachable) {
-        uint32_t lo = 0u, hi = top;                                 // count(hi) >= need
-        while (lo < hi) {
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            if (count_at(__uint_as_float(mid)) >= need) hi = mid;
-            else lo = mid + 1u;
-        }
-        level = lo;
-    }
-    const float lv = __uint_as_float(level);
-    // steps strictly below the level are all taken; those at the level in neuron order until the target is met
+    const bool at_start = st->at_start != 0;
+    const bool reachable = st->reachable != 0;
+    const float lv = __uint_as_float(reachable ? st->prefix : SEL_TOP);
+    const long long missing = st->missing;                          // among the steps at the level
     if (tid == 0) {
         star = D;
         star_before = 0;
     }
-    long long base = 0;
-    if (reachable) {
-        long long c = 0;
-        for (int i = tid; i < D; i += SEL_THREADS) {
-            const float *ki = key + (size_t)i * MS;
-            int lo = 0, hi = MS;                                    // steps with key < level
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (ki[mid] < lv) lo = mid + 1;
-                else hi = mid;
-            }
-            c += drop[(size_t)i * (MS + 1) + lo];
-        }
-        base = block_sum_i64(c, red);                               // < need
-    }
     __syncthreads();
-    // neurons in index order, SEL_THREADS at a time: prefix sums of the gains at the level
-    long long carried = base;
+    long long carried = 0;
     for (int i0 = 0; i0 < D && reachable; i0 += SEL_THREADS) {
         const int i = i0 + tid;
         long long gain = 0;
         if (i < D) {
             const float *ki = key + (size_t)i * MS;
-            int lo = 0, hi = MS;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (ki[mid] < lv) lo = mid + 1;
-                else hi = mid;
-            }
-            const int up = steps_up_to(ki, MS, lv);
-            gain = (long long)drop[(size_t)i * (MS + 1) + up] - drop[(size_t)i * (MS + 1) + lo];
+            const int32_t *di = drop + (size_t)i * (MS + 1);
+            gain = (long long)di[steps_below<true>(ki, MS, lv)] - di[steps_below<false>(ki, MS, lv)];
         }
         long long inc = gain;                                       // inclusive scan inside the wave
 #pragma unroll
@@ -262,8 +312,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_calib_select(const float *__res
         for (int q = 0; q < wave; ++q) before += wave_tot[q];
         long long chunk_total = 0;
         for (int q = 0; q < SEL_THREADS / 64; ++q) chunk_total += wave_tot[q];
-        const long long excl = before + inc - gain;                 // pairs dropped before this neuron's level steps
-        if (i < D && excl < need && excl + gain >= need) {
+        const long long excl = before + inc - gain;                 // found before this neuron's steps at the level
+        if (i < D && excl < missing && excl + gain >= missing) {
             star = i;                                               // exactly one neuron satisfies this
             star_before = excl;
         }
@@ -274,30 +324,22 @@ __global__ __launch_bounds__(SEL_THREADS) void k_calib_select(const float *__res
     __syncthreads();
     const int istar = star;
     const long long sb = star_before;
-    int taken = 0;
+    long long taken = 0;
     for (int i = tid; i < D; i += SEL_THREADS) {
         const float *ki = key + (size_t)i * MS;
         const int32_t *di = drop + (size_t)i * (MS + 1);
         int J;
-        if (c0 >= need) {
+        if (at_start) {
             J = 0;
         } else if (!reachable) {
-            J = steps_up_to(ki, MS, lv);                            // every finite step: the target cannot be met
+            J = steps_below<true>(ki, MS, lv);                      // every finite step: the target cannot be met
+        } else if (i < istar) {
+            J = steps_below<true>(ki, MS, lv);
         } else {
-            int lo = 0, hi = MS;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (ki[mid] < lv) lo = mid + 1;
-                else hi = mid;
-            }
-            if (i < istar) {
-                J = steps_up_to(ki, MS, lv);
-            } else if (i > istar) {
-                J = lo;
-            } else {
-                J = lo;
+            J = steps_below<false>(ki, MS, lv);
+            if (i == istar) {
                 long long c = sb;
-                while (c < need) {                                  // its steps at the level, one at a time
+                while (c < missing) {                               // its steps at the level, one at a time
                     c += di[J + 1] - di[J];
                     ++J;
                 }

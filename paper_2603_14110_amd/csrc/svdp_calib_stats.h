@@ -30,7 +30,7 @@ enum GemmEpilogue { EPI_DAMAGE = 0, EPI_SPLIT3 = 1, EPI_PLAIN = 2 };
 // EPI_SPLIT3: c1 -> three bf16 terms at planes[m*ldo + {0, N, 2N} + n]
 // EPI_PLAIN : out[m*ldo + n] = c1
 template <int NA, int EPI>
-__global__ __launch_bounds__(GM_THREADS) void k_gemm_nt(const bf16 *__restrict__ A1, const bf16 *__restrict__ A2, int lda,
+__global__ __launch_bounds__(GM_THREADS, 2) void k_gemm_nt(const bf16 *__restrict__ A1, const bf16 *__restrict__ A2, int lda,
                                                         int Ka, const bf16 *__restrict__ Bm, int ldb, int M, int N, int K,
                                                         const float *__restrict__ scale, float *__restrict__ out,
                                                         uint16_t *__restrict__ planes, int ldo)
