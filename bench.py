@@ -135,8 +135,10 @@ def run_layer(a, torch, np, binding, cost, synth):
     def rows_only(k):          # the dominant kernel by itself, on the mask words the steps produced
         binding.active_rows(copies[k % len(copies)], Xd[k], MASK[k], ws=ws)
 
+    plain = [c.with_flags(0) for c in copies]        # the dense baseline never takes the pipeline flags
+
     def dense_step(k):
-        binding.dense_ffn(copies[k % len(copies)], Xd[k], ws=ws, out=Y[k])
+        binding.dense_ffn(plain[k % len(plain)], Xd[k], ws=ws, out=Y[k])
 
     ms, all_ms = time_graph(torch, sparse_step, K, a.warmup, a.reps, not a.no_graph)
     nnz = NNZ.cpu().numpy().reshape(-1).astype(np.int64)
@@ -144,10 +146,26 @@ def run_layer(a, torch, np, binding, cost, synth):
     Kd = min(K, 128)
     ms_dense, _ = time_graph(torch, dense_step, Kd, min(a.warmup, 8), max(3, a.reps // 2), not a.no_graph)
     bytes_mean = float(np.mean([cost.bytes_sparse(spec.d, spec.D, spec.r, int(n), B, w) for n in nnz]))
+    rows_bytes = float(np.mean(cost.bytes_rows(spec.d, nnz, w)))
+    alive = None
+    if a.flags & binding.FLAG_REVALIDATE:
+        # sequential pipeline: rows really read = gate rows of the list + up/down rows of those whose gate is
+        # positive for some token of the batch (signs from an fp32 product of the stored values)
+        Wg32 = base.tensors["W_gate"].float()
+        bits = torch.arange(64, device="cuda", dtype=torch.int64)
+        alive = np.zeros(K, dtype=np.int64)
+        for k in range(K):
+            on = ((MASK[k][:, None] >> bits[None, :]) & 1).reshape(-1).bool()
+            pos = (Xd[k].float() @ Wg32.T > 0).any(dim=0)
+            alive[k] = int((on & pos).sum().item())
+        del Wg32
+        rows_bytes = float(np.mean(cost.bytes_rows_sequential(spec.d, nnz, alive, w)))
+        bytes_mean += rows_bytes - float(np.mean(cost.bytes_rows(spec.d, nnz, w)))
     res = dict(
         us_step=ms * 1e3 / K, us_dense=ms_dense * 1e3 / Kd, bytes_step=bytes_mean,
         bytes_dense=cost.bytes_dense(spec.d, spec.D, B, w), layers=1, all_ms=all_ms,
-        density=nnz / spec.D, us_rows=ms_rows * 1e3 / K, bytes_rows=float(np.mean(cost.bytes_rows(spec.d, nnz, w))),
+        density=nnz / spec.D, us_rows=ms_rows * 1e3 / K, bytes_rows=rows_bytes,
+        alive_density=None if alive is None else alive / spec.D,
         workload=f"{spec.name}-shaped layer d={spec.d} D={spec.D} r={spec.r} batch={B}, {K} decode steps, "
                  f"~{spec.sparsity:.0%} activation sparsity per token",
         dtype=spec.dtype, cache_mode="cold" if len(copies) > 1 else "hot", copies=len(copies),
@@ -405,6 +423,7 @@ def main():
                    "engine": a.engine,
                    "storage": "bf16 weights/tokens, f32 accumulate" if r["dtype"] == "bf16" else "f32"},
         "density_mean": float(dens.mean()),
+        "density_after_gate_mean": None if r.get("alive_density") is None else float(r["alive_density"].mean()),
         "density_percentiles_0_5_50_95_100": [float(np.percentile(dens, p)) for p in (0, 5, 50, 95, 100)],
         "dense_us_per_step": us_dense,
         "dense_us_per_token_per_layer": us_dense / B / Lyr,

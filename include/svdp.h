@@ -60,10 +60,15 @@ typedef enum {
 enum {
     /* dReLU variant (paper Sec. 5.1, eq. 6): ReLU is applied to the up branch too. */
     SVDP_FLAG_DRELU = 1u,
-    /* Sequential pipeline (paper Sec. 4.2, "Gate/up execution order"): after the
-     * gate product of a predicted-active neuron is known, its W_down row is
-     * skipped when the gate is <= 0 for every token of the batch.  The output is
-     * unchanged (such a neuron contributes exactly zero).                         */
+    /* Sequential pipeline (paper Sec. 4.2, "Gate/up execution order"): the gate
+     * product of a predicted-active neuron re-validates the prediction; when it is
+     * <= 0 for every token of the batch, neither its W_up row nor its W_down row
+     * is read.  The output is unchanged (such a neuron contributes exactly zero);
+     * what changes is the bytes read: d*w per listed neuron for the gate, 2*d*w more
+     * only for those that survive.  Pays when the predictor over-predicts (low rank,
+     * cautious bias); costs one more dependent fetch per row otherwise.  In the
+     * default launch organisation a dedicated row kernel runs (vector units); the
+     * optional organisations skip the W_down row only.                             */
     SVDP_FLAG_REVALIDATE = 2u
 };
 

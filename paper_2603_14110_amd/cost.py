@@ -31,6 +31,12 @@ def bytes_rows(d: int, nnz: int, w: int) -> int:
     return 3 * nnz * d * w
 
 
+def bytes_rows_sequential(d: int, nnz, alive, w: int):
+    """Sequential pipeline (Sec. 4.2): the gate row of every listed neuron, the up and down rows only of
+    the `alive` ones whose gate came out positive."""
+    return (nnz + 2 * alive) * d * w
+
+
 def bytes_io(d: int, B: int, w: int) -> int:
     """x in (storage dtype) and y out (fp32)."""
     return B * d * w + 4 * B * d

@@ -7,6 +7,7 @@
 #include "svdp_kernels.h"
 #include "svdp_fused.h"
 #include "svdp_rows_mfma.h"
+#include "svdp_rows_seq.h"
 #include "svdp_calib.h"
 #include "svdp_calib_stats.h"
 
@@ -254,6 +255,24 @@ bool launch_rows_matrix(const svdp_layer *L, const void *x, int B, const uint64_
     }
 }
 
+// The row kernel of the sequential pipeline (SVDP_FLAG_REVALIDATE), launched in place of k_rows.
+template <typename W, int NB, int MODE>
+svdp_status launch_rows_seq(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
+                            const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w,
+                            hipStream_t st)
+{
+    const int d = L->d, D = L->D, grid = ROWS_BLOCKS;
+    const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
+    const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)2 * NB * max_chunk + (size_t)3 * max_chunk) * 4;
+    static int granted = 64 * 1024;
+    if (allow_lds(k_rows_seq<W, NB, MODE>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_rows_seq<W, NB, MODE>), dim3(grid), dim3(ROWS_THREADS), lds, st,
+                       static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
+                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, mask, idx_in, nnz_in,
+                       idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart);
+    return hip_status(hipSuccess);
+}
+
 template <typename W, int NB, int MODE>
 svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
                         const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base,
@@ -293,7 +312,9 @@ svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_
         }
     }
     svdp_status s;
-    if (!launch_rows_matrix<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st, &s)) {
+    if ((L->flags & SVDP_FLAG_REVALIDATE) != 0) {
+        s = launch_rows_seq<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st);
+    } else if (!launch_rows_matrix<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st, &s)) {
         static int granted = 64 * 1024;
         if (allow_lds(k_rows<W, NB, MODE, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
         hipLaunchKernelGGL((k_rows<W, NB, MODE, false>), dim3(grid), dim3(ROWS_THREADS), lds, st, Wg, Wu, Wd, xs, B, d,
@@ -448,6 +469,8 @@ svdp_status launch_rows_only(const svdp_layer *L, const void *x, int B, const ui
     const int grid = ROWS_BLOCKS;
     const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
     const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
+    if ((L->flags & SVDP_FLAG_REVALIDATE) != 0)
+        return launch_rows_seq<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, st);
     svdp_status sm;
     if (launch_rows_matrix<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, st, &sm)) return sm;
     static int granted = 64 * 1024;

@@ -277,6 +277,49 @@ def test_flags_drelu_and_revalidate(env):
         assert np.array_equal(y_plain.cpu().numpy(), y_rev.cpu().numpy())
 
 
+@pytest.mark.parametrize("name,over", SMALL)
+def test_sequential_pipeline(env, name, over):
+    """SVDP_FLAG_REVALIDATE in the default launch organisation (its own row kernel): every entry point
+    against the oracle, lists with many false positives (up to all D rows), and the values of the
+    parallel pipeline bit for bit on the vector engine (the dropped terms are exact zeros)."""
+    binding, torch, oracle = env
+    c = get_case(env, name, **over)
+    D = c.spec.D
+    seq = c.dev.with_flags(binding.FLAG_REVALIDATE)
+    seq_d = c.dev.with_flags(binding.FLAG_REVALIDATE | binding.FLAG_DRELU)
+    rng = np.random.default_rng(11)
+    lists = [np.zeros(0, np.int32), np.arange(D, dtype=np.int32), np.arange(1, D, 3, dtype=np.int32),
+             np.sort(rng.choice(D, D // 2 + 1, replace=False)).astype(np.int32), rng.permutation(D)[:300].astype(np.int32)]
+    binding.set_engine(binding.ENGINE_VECTOR)
+    try:
+        for B in (1, 2, 5, 8):
+            x = c.Xd[7:7 + B]
+            Xf = c.X[7:7 + B]
+            for t0 in (0, 16):                       # offsets the union-batch step tests also use
+                step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE, modes=(0,))
+                if B <= 4:
+                    step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE | binding.FLAG_DRELU, modes=(0,))
+            assert torch.equal(binding.ffn_step(seq, x), binding.ffn_step(c.dev, x))
+            for lst in lists:
+                idx = torch.zeros(D, dtype=torch.int32, device="cuda")
+                idx[: lst.size] = torch.from_numpy(lst).cuda()
+                nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
+                y = binding.sparse_ffn(seq, x, idx, nnz)
+                y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf, lst)
+                parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, lst))
+                assert torch.equal(y, binding.sparse_ffn(c.dev, x, idx, nnz))
+                yd = binding.sparse_ffn(seq_d, x, idx, nnz).cpu().numpy()
+                parity.check_y(yd, oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf, lst, drelu=True),
+                               c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, lst))
+            # the dense entry point with the flag: every row's gate decides for itself (no predictor involved)
+            yd = binding.dense_ffn(seq, x)
+            parity.check_y(yd.cpu().numpy(), oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf),
+                           c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, np.arange(D)))
+            assert torch.equal(yd, binding.dense_ffn(c.dev, x))
+    finally:
+        binding.set_engine(binding.ENGINE_AUTO)
+
+
 def test_deterministic(env):
     """Fixed summation order (App. C): bitwise identical output run to run."""
     binding, torch, _ = env
