@@ -500,7 +500,8 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
         for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
 
     const bool drelu = (flags & 1u) != 0;
-    const bool revalidate = (flags & 2u) != 0;
+    // the sequential pipeline has its own kernel (k_rows_seq); here only the in-launch-reduction variant skips rows
+    const bool revalidate = FINISH && (flags & 2u) != 0;
     auto row_of = [&](int q) -> size_t {
         return MODE == ROWS_DENSE ? (size_t)(lo + min(q, cnt - 1)) : (size_t)lidx[q];
     };
