@@ -89,6 +89,32 @@ def test_validation_rejects_before_any_launch(svdp):
     assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, 0x1000, 0x1000, 64, None) == WORKSPACE
 
 
+def test_calibration_entry_points_validate_on_the_host(svdp):
+    L = svdp.lib()
+    INVALID, UNSUPPORTED, WORKSPACE = 1, 2, 3
+    wb = L.svdp_calib_workspace_bytes(11008, 2048, 16)
+    # running maxima, dropped counts and thresholds per step of every neuron
+    assert wb % 256 == 0 and wb >= 11008 * (128 * 4 + 2 * 129 * 4 + 4)
+    assert L.svdp_calib_workspace_bytes(11008, 4096, 1) > wb
+    for bad in ((0, 16, 1), (4, 0, 1), (4, 4097, 1), (4, 16, 0)):
+        assert L.svdp_calib_workspace_bytes(*bad) == 0
+    a = 0x1000
+    assert L.svdp_calib_bias(None, a, 4, 8, 1, 3, a, None, None, None, a, 1 << 20, None) == INVALID
+    assert L.svdp_calib_bias(a, a, 4, 8, 1, -1, a, None, None, None, a, 1 << 20, None) == INVALID
+    assert L.svdp_calib_bias(a, a, 4, 8, 0, 3, a, None, None, None, a, 1 << 20, None) == INVALID
+    assert L.svdp_calib_bias(a, a, 4, 5000, 1, 3, a, None, None, None, a, 1 << 30, None) == UNSUPPORTED
+    assert L.svdp_calib_bias(a, a, 4, 8, 1, 3, a, None, None, None, None, 1 << 20, None) == WORKSPACE
+    assert L.svdp_calib_bias(a, a, 4, 8, 1, 3, a, None, None, None, a, 16, None) == WORKSPACE
+    l = _layer(svdp)
+    ws = L.svdp_calib_stats_workspace_bytes(ctypes.byref(l), 2048)
+    assert ws % 256 == 0 and ws >= 256 * 4096 * 2 + 11008 * 4 + 2048 * 3 * 256 * 2
+    assert L.svdp_calib_stats_workspace_bytes(ctypes.byref(_layer(svdp, dt=0)), 2048) == 0      # bf16 only
+    assert L.svdp_calib_stats_workspace_bytes(ctypes.byref(l), 0) == 0
+    assert L.svdp_calib_stats(ctypes.byref(l), None, 8, a, a, a, ws, None) == INVALID
+    assert L.svdp_calib_stats(ctypes.byref(_layer(svdp, dt=0, d=4096)), a, 8, a, a, a, 1 << 30, None) == UNSUPPORTED
+    assert L.svdp_calib_stats(ctypes.byref(l), a, 8, a, a, a, 64, None) == WORKSPACE
+
+
 def test_binding_fails_loudly_without_library(svdp, monkeypatch):
     monkeypatch.setattr(svdp, "_lib", None)
     monkeypatch.setattr(svdp, "LIB_PATH", "/nonexistent/libsvdp.so")
