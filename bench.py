@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--copies", type=int, default=16, help="weight copies rotated through (1 = hot cache)")
     ap.add_argument("--reps", type=int, default=5, help="graph replays; the median is reported")
     ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--glue-launches", action="store_true",
+                    help="--workload stack: the glue between layers as launches of its own (default: inside the "
+                         "next layer's first kernel)")
     ap.add_argument("--engine", default="auto", choices=["auto", "vector", "matrix"],
                     help="arithmetic units of the batch-sensitive kernels (svdp_set_engine)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -193,7 +196,7 @@ def run_stack(a, torch, np, binding, cost, synth):
         print(f"[bench] layer {i + 1}/{len(specs)} ready (target sparsity {sp.sparsity:.3f})", file=sys.stderr, flush=True)
     shifts = [torch.from_numpy((2.0 * u_all[i + 1]).astype(np.float32)).cuda() for i in range(len(specs) - 1)]
     shifts.append(torch.zeros(specs[0].d, dtype=torch.float32, device="cuda"))
-    st = stack.FFNStack(dev_layers, shifts)
+    st = stack.FFNStack(dev_layers, shifts, fused_glue=not a.glue_launches)
     X_st = synth.timed_tokens(L0, K)
     Xd = binding.to_device(X_st, "bf16")
     NNZ = torch.zeros((K, len(specs), 1), dtype=torch.int32, device="cuda")

@@ -190,7 +190,8 @@ svdp_status svdp_step_timeouts(int32_t *count);
 /* Glue between stacked layers used by the stacked benchmark (not from the
  * paper): v = x + y; x_next = v / sqrt(mean(v^2) + eps) + shift, rounded to
  * `dtype`.  x: device [d] in `dtype`; y: device [d] fp32; shift: device [d]
- * fp32; x_next: device [d] in `dtype` (may alias x).                            */
+ * fp32; x_next: device [d] in `dtype` (may alias x).  d must be a multiple of 8
+ * (bf16) or 4 (fp32), all four pointers 16-byte aligned.                       */
 svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift,
                             int32_t d, int32_t dtype, float eps, void *x_next,
                             void *stream);
@@ -227,6 +228,18 @@ svdp_status svdp_calib_stats(const svdp_layer *layer, const void *X, int32_t T, 
 svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
                             float *b, int32_t *k, int32_t *steps, float *kendall,
                             void *ws, size_t ws_bytes, void *stream);
+
+/* svdp_ffn_step with svdp_stack_glue in front of it, in the same launches: the step's token is
+ * x = RMSNorm(x_prev + y_prev) + shift rounded to `wdtype` (bit for bit what svdp_stack_glue writes),
+ * formed inside the step's first kernel, which saves the glue's own launch between stacked layers.
+ * x_prev [B][d] in `wdtype`, y_prev [B][d] fp32, shift [d] fp32 (shared by the tokens): device, read;
+ * x_out [B][d] in `wdtype`: device, receives x (must not alias x_prev or y_prev; the row kernel reads it).
+ * The other arguments as in svdp_ffn_step; y may alias y_prev.  Always the kernel sequence
+ * (SVDP_STEP_PERSISTENT does not apply).                                                          */
+svdp_status svdp_ffn_step_glued(const svdp_layer *layer, const void *x_prev, const float *y_prev,
+                                const float *shift, float eps, void *x_out, int32_t B, float *y,
+                                uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /* Static string for a status code.  Never NULL. */
 const char *svdp_status_string(svdp_status st);

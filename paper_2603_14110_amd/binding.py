@@ -25,7 +25,7 @@ EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
     "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version", "svdp_set_step_mode",
     "svdp_step_timeouts", "svdp_active_rows", "svdp_set_engine", "svdp_calib_workspace_bytes", "svdp_calib_bias",
-    "svdp_calib_stats_workspace_bytes", "svdp_calib_stats",
+    "svdp_calib_stats_workspace_bytes", "svdp_calib_stats", "svdp_ffn_step_glued",
 ]
 
 
@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
     L.svdp_calib_stats_workspace_bytes.restype = ctypes.c_size_t
     L.svdp_calib_stats.argtypes = [lp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
     L.svdp_calib_stats.restype = ctypes.c_int
+    L.svdp_ffn_step_glued.argtypes = [lp, vp, vp, vp, ctypes.c_float, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.svdp_ffn_step_glued.restype = ctypes.c_int
     L.svdp_set_engine.argtypes = [i32]
     L.svdp_set_engine.restype = None
     L.svdp_step_timeouts.argtypes = [ctypes.POINTER(ctypes.c_int32)]
@@ -226,6 +228,22 @@ def ffn_step(layer: DeviceLayer, x: torch.Tensor, ws: Optional[torch.Tensor] = N
     y = torch.empty((B, layer.d), dtype=torch.float32, device=x.device) if out is None else out
     _check(lib().svdp_ffn_step(ctypes.byref(layer.c), _ptr(x), B, _ptr(y), _ptr(mask), _ptr(idx), _ptr(nnz),
                                _ptr(ws), ws.numel(), _stream()), "svdp_ffn_step")
+    return y
+
+
+def ffn_step_glued(layer: DeviceLayer, x_prev: torch.Tensor, y_prev: torch.Tensor, shift: torch.Tensor,
+                   x_out: torch.Tensor, eps: float = 1e-6, ws: Optional[torch.Tensor] = None,
+                   out: Optional[torch.Tensor] = None, mask: Optional[torch.Tensor] = None,
+                   idx: Optional[torch.Tensor] = None, nnz: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The step on x = RMSNorm(x_prev + y_prev) + shift (written to x_out), glue and step in the same launches."""
+    x_prev, B = _x2(layer, x_prev)
+    assert y_prev.numel() == B * layer.d and x_out.numel() == B * layer.d and shift.numel() == layer.d
+    assert x_out.dtype == x_prev.dtype and y_prev.dtype == torch.float32 and shift.dtype == torch.float32
+    ws = layer.workspace(B) if ws is None else ws
+    y = torch.empty((B, layer.d), dtype=torch.float32, device=x_prev.device) if out is None else out
+    _check(lib().svdp_ffn_step_glued(ctypes.byref(layer.c), _ptr(x_prev), _ptr(y_prev), _ptr(shift), float(eps),
+                                     _ptr(x_out), B, _ptr(y), _ptr(mask), _ptr(idx), _ptr(nnz), _ptr(ws), ws.numel(),
+                                     _stream()), "svdp_ffn_step_glued")
     return y
 
 

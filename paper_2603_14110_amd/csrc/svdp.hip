@@ -155,8 +155,17 @@ uint32_t *ctrl_for(const void *ws)
 
 // ---- launch helpers, one per kernel, templated on storage type and batch capacity ----
 
+// The stacked benchmark's glue folded into the first kernel of a step (svdp_ffn_step_glued).
+struct GlueArgs {
+    const float *y_prev;
+    const float *shift;
+    float eps;
+    void *x_out;
+};
+
 template <typename W, int NB>
-svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, int *nt_out, hipStream_t st)
+svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, int *nt_out, hipStream_t st,
+                      const GlueArgs *glue = nullptr)
 {
     constexpr int VEC = Elem<W>::VEC;
     const int d = L->d, r = L->r;
@@ -166,10 +175,18 @@ svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, i
     const size_t parts = XP_THREADS / outs >= 1 ? XP_THREADS / outs : 1;
     const size_t nsub = XP_THREADS / (XP_COLS / VEC);
     const size_t lds = ((size_t)NB * XP_ROWS + nsub * (outs + 1) + parts * outs) * 4;
-    static int granted = 64 * 1024;
-    if (allow_lds(k_xP<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_xP<W, NB>), dim3(nt, ncs), dim3(XP_THREADS), lds, st, static_cast<const W *>(L->P),
-                       static_cast<const W *>(x), B, d, r, tpart);
+    static int granted = 64 * 1024, granted_g = 64 * 1024;
+    if (glue != nullptr) {
+        if (allow_lds(k_xP<W, NB, true>, lds, &granted_g) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((k_xP<W, NB, true>), dim3(nt, ncs), dim3(XP_THREADS), lds, st, static_cast<const W *>(L->P),
+                           static_cast<const W *>(x), B, d, r, tpart, glue->y_prev, glue->shift, glue->eps,
+                           static_cast<W *>(glue->x_out));
+    } else {
+        if (allow_lds(k_xP<W, NB, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((k_xP<W, NB, false>), dim3(nt, ncs), dim3(XP_THREADS), lds, st,
+                           static_cast<const W *>(L->P), static_cast<const W *>(x), B, d, r, tpart, nullptr, nullptr,
+                           0.f, nullptr);
+    }
     *nt_out = nt;
     return hip_status(hipSuccess);
 }
@@ -413,10 +430,10 @@ svdp_status run_step_fused(const svdp_layer *L, const void *x, int B, float *y, 
 
 template <typename W, int NB>
 svdp_status run_predict(const svdp_layer *L, const void *x, int B, float *s, uint64_t *mask, const Workspace &w,
-                        hipStream_t st)
+                        hipStream_t st, const GlueArgs *glue = nullptr)
 {
     int nt = 0;
-    svdp_status e = launch_xP<W, NB>(L, x, B, w.tpart, &nt, st);
+    svdp_status e = launch_xP<W, NB>(L, x, B, w.tpart, &nt, st, glue);
     if (e != SVDP_OK) return e;
     if (NB >= 4 && nt > 1 && !scores_on_matrix<W, NB>(L)) {
         // finish t once instead of in every score block (the vector score kernel splits the
@@ -433,8 +450,17 @@ svdp_status run_predict(const svdp_layer *L, const void *x, int B, float *s, uin
 
 template <typename W, int NB>
 svdp_status run_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
-                     int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
+                     int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st,
+                     const GlueArgs *glue = nullptr)
 {
+    if (glue != nullptr) {
+        // x is made by the first kernel (from x_prev = x); the row kernel reads it from x_out
+        uint64_t *mask = mask_out ? mask_out : w.mask;
+        svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st, glue);
+        if (e != SVDP_OK) return e;
+        return launch_rows<W, NB, ROWS_MASK>(L, glue->x_out, B, mask, nullptr, nullptr, idx_out, nnz_out, w, ws_base, y,
+                                             st);
+    }
     if (g_fused_mode.load() == SVDP_STEP_PERSISTENT) {
         const svdp_status f = run_step_fused<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st);
         if (f != SVDP_ERR_UNSUPPORTED) return f;
@@ -487,9 +513,11 @@ svdp_status dispatch_rows_only(const svdp_layer *L, const void *x, int B, const 
     SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows_only<W, NB>(L, x, B, mask, w, st)));
 }
 svdp_status dispatch_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out,
-                          int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
+                          int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st,
+                          const GlueArgs *glue = nullptr)
 {
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (run_step<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st)));
+    SVDP_DISPATCH(L->wdtype, nb_of(B),
+                  (run_step<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st, glue)));
 }
 
 inline bool bad_batch(int B) { return B < 1 || B > SVDP_MAX_BATCH; }
@@ -567,6 +595,22 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
     return dispatch_step(layer, x, B, y, mask_out, idx_out, nnz_out, w, ws, static_cast<hipStream_t>(stream));
 }
 
+svdp_status svdp_ffn_step_glued(const svdp_layer *layer, const void *x_prev, const float *y_prev, const float *shift,
+                                float eps, void *x_out, int32_t B, float *y, uint64_t *mask_out, int32_t *idx_out,
+                                int32_t *nnz_out, void *ws, size_t ws_bytes, void *stream)
+{
+    svdp_status st = check_layer(layer, true, true);
+    if (st != SVDP_OK) return st;
+    if (x_prev == nullptr || y_prev == nullptr || shift == nullptr || x_out == nullptr || y == nullptr ||
+        bad_batch(B) || !aligned16(x_prev) || !aligned16(x_out) || !aligned16(y) || !(eps >= 0.f))
+        return SVDP_ERR_INVALID_ARG;
+    Workspace w;
+    st = check_ws(layer, B, ws, ws_bytes, &w);
+    if (st != SVDP_OK) return st;
+    const GlueArgs glue{y_prev, shift, eps, x_out};
+    return dispatch_step(layer, x_prev, B, y, mask_out, idx_out, nnz_out, w, ws, static_cast<hipStream_t>(stream), &glue);
+}
+
 svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask, void *ws,
                              size_t ws_bytes, void *stream)
 {
@@ -583,12 +627,16 @@ svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift, i
                             void *x_next, void *stream)
 {
     if (x == nullptr || y == nullptr || shift == nullptr || x_next == nullptr || d <= 0) return SVDP_ERR_INVALID_ARG;
+    if (dtype != SVDP_F32 && dtype != SVDP_BF16) return SVDP_ERR_UNSUPPORTED;
+    // whole 16-byte vectors of x, as for a layer's d
+    if (d % (dtype == SVDP_BF16 ? 8 : 4) != 0) return SVDP_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(shift) || !aligned16(x_next)) return SVDP_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == SVDP_F32)
-        hipLaunchKernelGGL(k_stack_glue<float>, dim3(1), dim3(1024), 0, st, static_cast<const float *>(x), y, shift,
+        hipLaunchKernelGGL(k_stack_glue<float>, dim3(1), dim3(256), 0, st, static_cast<const float *>(x), y, shift,
                            d, eps, static_cast<float *>(x_next));
     else if (dtype == SVDP_BF16)
-        hipLaunchKernelGGL(k_stack_glue<bf16>, dim3(1), dim3(1024), 0, st, static_cast<const bf16 *>(x), y, shift, d,
+        hipLaunchKernelGGL(k_stack_glue<bf16>, dim3(1), dim3(256), 0, st, static_cast<const bf16 *>(x), y, shift, d,
                            eps, static_cast<bf16 *>(x_next));
     else
         return SVDP_ERR_UNSUPPORTED;

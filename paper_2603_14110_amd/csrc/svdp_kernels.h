@@ -21,6 +21,44 @@ constexpr int SCAN_THREADS = 1024;   // k_compact_scan block
 constexpr int RED_COLS = 8;          // k_reduce_y: float4 columns per block (one 128-byte line per partial row)
 constexpr int RED_SEGS = 128;        // k_reduce_y: segments of the partial list per block
 
+// Sum over j < d of (x[j] + y[j])^2 by a block of 256 threads in a fixed order (a thread takes the
+// 16-byte vectors t, t + 256, ... of x in ascending order, then the lanes of a wave, then the four
+// waves): the mean square of the stacked benchmark's glue.  Every thread gets the total.
+// part: 4 floats of shared memory.  d is a multiple of the vector length.
+__device__ __forceinline__ float glue_block_total(float ss, float *part)
+{
+    const int tid = threadIdx.x;
+    ss = wave_sum(ss);
+    __syncthreads();
+    if ((tid & 63) == 0) part[tid >> 6] = ss;
+    __syncthreads();
+    return ((part[0] + part[1]) + part[2]) + part[3];
+}
+
+template <typename W>
+__device__ __forceinline__ float glue_sum_squares(const W *__restrict__ x, const float *__restrict__ y, int d,
+                                                  float *part)
+{
+    constexpr int VEC = Elem<W>::VEC;
+    float ss = 0.f;
+#pragma unroll 2
+    for (int v = threadIdx.x; v < d / VEC; v += 256) {
+        float xv[VEC];
+        load_vec(x + (size_t)v * VEC, xv);
+#pragma unroll
+        for (int e4 = 0; e4 < VEC / 4; ++e4) {
+            const float4 yv = *reinterpret_cast<const float4 *>(y + (size_t)v * VEC + 4 * e4);
+            const float a = xv[4 * e4] + yv.x, b = xv[4 * e4 + 1] + yv.y, c = xv[4 * e4 + 2] + yv.z,
+                        dd = xv[4 * e4 + 3] + yv.w;
+            ss = fmaf(a, a, ss);
+            ss = fmaf(b, b, ss);
+            ss = fmaf(c, c, ss);
+            ss = fmaf(dd, dd, ss);
+        }
+    }
+    return glue_block_total(ss, part);
+}
+
 // ---------------------------------------------------------------------------
 // Predictor stage 1: partial t = x P over a tile of P   (Sec. 4.1 eq. 2: the
 // inner factor B x of A B x + b, with P = B^T).
@@ -30,9 +68,17 @@ constexpr int RED_SEGS = 128;        // k_reduce_y: segments of the partial list
 // before x is staged, and the NSUB row-partials are added through LDS in order.
 // Dynamic LDS: NB*XP_ROWS + NSUB*(NB*XP_COLS + 1) + PARTS*NB*XP_COLS floats.
 // ---------------------------------------------------------------------------
-template <typename W, int NB>
+// With GLUE the token is not given but made here: x = RMSNorm(x_prev + y_prev) + shift rounded to
+// the storage type, the stacked benchmark's glue (k_stack_glue forms the mean square with the same
+// function, so the two give the same bits).  Every block forms the norm itself from the d sums of x_prev
+// and y_prev (a few KB from L2) instead of waiting for one more launch; the blocks of the first
+// column tile also write x to x_out for the row kernel.
+template <typename W, int NB, bool GLUE>
 __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, const W *__restrict__ x,
-                                                   int B, int d, int r, float *__restrict__ tpart)
+                                                   int B, int d, int r, float *__restrict__ tpart,
+                                                   const float *__restrict__ y_prev,
+                                                   const float *__restrict__ shift, float eps,
+                                                   W *__restrict__ x_out)
 {
     constexpr int VEC = Elem<W>::VEC;
     constexpr int CG = XP_COLS / VEC;          // column groups per tile
@@ -55,12 +101,38 @@ __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, cons
         const int j = j0 + sub + k * NSUB;
         if (colok && j < d) raw[k] = load_raw(P + (size_t)j * r + col);
     }
+    __shared__ float gpart[4];
+    float inv[NB];
+    if (GLUE) {
+        static_assert(XP_THREADS == 256, "glue_sum_squares is written for 256 threads");
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            inv[b] = 0.f;
+            if (b < B) {
+                const float tot = glue_sum_squares(x + (size_t)b * d, y_prev + (size_t)b * d, d, gpart);
+                inv[b] = 1.0f / sqrtf(tot / (float)d + eps);
+            }
+        }
+    }
     // x of the tile's rows, one 16-byte vector per thread and pass (d is a multiple of VEC)
     for (int i = tid; i < NB * (XP_ROWS / VEC); i += XP_THREADS) {
         const int b = i / (XP_ROWS / VEC), j = j0 + (i % (XP_ROWS / VEC)) * VEC;
         float w[VEC];
         if (b < B && j < d) {
             load_vec(x + (size_t)b * d + j, w);
+            if (GLUE) {
+                W rounded[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float v = (w[e] + y_prev[(size_t)b * d + j + e]) * inv[b] + shift[j + e];
+                    from_f32(v, &rounded[e]);
+                    w[e] = to_f32(rounded[e]);
+                }
+                if (blockIdx.y == 0) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) x_out[(size_t)b * d + j + e] = rounded[e];
+                }
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) w[e] = 0.f;
@@ -774,27 +846,66 @@ __global__ __launch_bounds__(RED_COLS *RED_SEGS) void k_reduce_y(const float *__
 // One block; the sum of squares is reduced in a fixed order.
 // ---------------------------------------------------------------------------
 template <typename W>
-__global__ __launch_bounds__(1024) void k_stack_glue(const W *x, const float *__restrict__ y,
-                                                     const float *__restrict__ shift, int d, float eps,
-                                                     W *x_next)
+__global__ __launch_bounds__(256) void k_stack_glue(const W *x, const float *__restrict__ y,
+                                                    const float *__restrict__ shift, int d, float eps, W *x_next)
 {
-    __shared__ float part[16];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float ss = 0.f;
-    for (int j = tid; j < d; j += 1024) {
-        const float v = to_f32(x[j]) + y[j];
-        ss = fmaf(v, v, ss);
+    constexpr int VEC = Elem<W>::VEC;
+    constexpr int KEEP = 4;                            // vectors of x + y a thread keeps in registers
+    __shared__ float part[4];
+    const int tid = threadIdx.x, nvec = d / VEC;
+    // one trip to memory for x, y and the shift of the thread's first KEEP vectors; the sum of squares
+    // in the order of glue_sum_squares (the thread's vectors ascending, their elements ascending)
+    float v[KEEP][VEC], sh[KEEP][VEC];
+#pragma unroll
+    for (int k = 0; k < KEEP; ++k) {
+        const int vi = tid + k * 256;
+        if (vi < nvec) {
+            load_vec(x + (size_t)vi * VEC, v[k]);
+#pragma unroll
+            for (int e4 = 0; e4 < VEC / 4; ++e4) {
+                const float4 yv = *reinterpret_cast<const float4 *>(y + (size_t)vi * VEC + 4 * e4);
+                const float4 sv = *reinterpret_cast<const float4 *>(shift + (size_t)vi * VEC + 4 * e4);
+                v[k][4 * e4] += yv.x; v[k][4 * e4 + 1] += yv.y; v[k][4 * e4 + 2] += yv.z; v[k][4 * e4 + 3] += yv.w;
+                sh[k][4 * e4] = sv.x; sh[k][4 * e4 + 1] = sv.y; sh[k][4 * e4 + 2] = sv.z; sh[k][4 * e4 + 3] = sv.w;
+            }
+        }
     }
-    ss = wave_sum(ss);
-    if (lane == 0) part[wave] = ss;
-    __syncthreads();
-    float tot = 0.f;
-    for (int q = 0; q < 16; ++q) tot += part[q];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < KEEP; ++k)
+        if (tid + k * 256 < nvec) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) ss = fmaf(v[k][e], v[k][e], ss);
+        }
+    for (int vi = tid + KEEP * 256; vi < nvec; vi += 256) {
+        float xv[VEC];
+        load_vec(x + (size_t)vi * VEC, xv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float a = xv[e] + y[(size_t)vi * VEC + e];
+            ss = fmaf(a, a, ss);
+        }
+    }
+    const float tot = glue_block_total(ss, part);      // its barriers: every read of x above is done (x_next may alias x)
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-    __syncthreads();
-    for (int j = tid; j < d; j += 1024) {
-        const float v = (to_f32(x[j]) + y[j]) * inv + shift[j];
-        from_f32(v, &x_next[j]);
+    auto emit = [&](int vi, const float (&vv)[VEC], const float (&ss4)[VEC]) {
+        W outv[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) from_f32(vv[e] * inv + ss4[e], &outv[e]);
+        *reinterpret_cast<uint4 *>(x_next + (size_t)vi * VEC) = *reinterpret_cast<const uint4 *>(outv);
+    };
+#pragma unroll
+    for (int k = 0; k < KEEP; ++k)
+        if (tid + k * 256 < nvec) emit(tid + k * 256, v[k], sh[k]);
+    for (int vi = tid + KEEP * 256; vi < nvec; vi += 256) {   // a thread rewrites only the vector it reads here
+        float xv[VEC], sv[VEC];
+        load_vec(x + (size_t)vi * VEC, xv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            xv[e] += y[(size_t)vi * VEC + e];
+            sv[e] = shift[(size_t)vi * VEC + e];
+        }
+        emit(vi, xv, sv);
     }
 }
 

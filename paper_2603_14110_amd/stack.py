@@ -26,9 +26,13 @@ def stack_specs(n_layers: int, base: str = "7b", seed0: int = 4000, lo: float = 
 class FFNStack:
     """Device-resident stack; `step` runs every layer of one decode step on the current stream."""
 
-    def __init__(self, layers: List[binding.DeviceLayer], shifts: List[torch.Tensor], dense: bool = False):
+    def __init__(self, layers: List[binding.DeviceLayer], shifts: List[torch.Tensor], dense: bool = False,
+                 fused_glue: bool = True):
         assert len(shifts) == len(layers)
         self.layers, self.shifts, self.dense = layers, shifts, dense
+        # sparse stack: the glue between two layers runs inside the next layer's first kernel
+        # (svdp_ffn_step_glued) instead of as a launch of its own; same bits either way
+        self.fused_glue = fused_glue
         dev = layers[0].tensors["P"].device
         self.d, self.dtype = layers[0].d, layers[0].dtype
         self.ws = layers[0].workspace(1)
@@ -37,24 +41,32 @@ class FFNStack:
         self.nnz = torch.zeros((len(layers), 1), dtype=torch.int32, device=dev)
 
     @classmethod
-    def from_synth(cls, synth_layers, dense: bool = False):
+    def from_synth(cls, synth_layers, dense: bool = False, fused_glue: bool = True):
         dev_layers = [binding.DeviceLayer.from_synth(L) for L in synth_layers]
         shifts = [torch.from_numpy((2.0 * L.u).astype(np.float32)).cuda() for L in synth_layers[1:]]
         shifts.append(torch.zeros(synth_layers[0].spec.d, dtype=torch.float32, device="cuda"))
-        return cls(dev_layers, shifts, dense)
+        return cls(dev_layers, shifts, dense, fused_glue)
 
     def as_dense(self) -> "FFNStack":
         return FFNStack(self.layers, self.shifts, dense=True)
+
+    def with_glue_launches(self) -> "FFNStack":
+        return FFNStack(self.layers, self.shifts, dense=self.dense, fused_glue=False)
 
     def step(self, x0: torch.Tensor, nnz: Optional[torch.Tensor] = None) -> torch.Tensor:
         """x0: [d] in the activation dtype.  nnz: optional int32 [n_layers][1] receiving the
         list length of every layer.  Returns the stack output (a persistent buffer)."""
         nnz = self.nnz if nnz is None else nnz
         self.x[0].copy_(x0)
+        fused = self.fused_glue and not self.dense
         for l, layer in enumerate(self.layers):
             if self.dense:
                 binding.dense_ffn(layer, self.x[l], ws=self.ws, out=self.y)
+            elif fused and l > 0:
+                binding.ffn_step_glued(layer, self.x[l - 1], self.y, self.shifts[l - 1], self.x[l], ws=self.ws,
+                                       out=self.y, nnz=nnz[l])
             else:
                 binding.ffn_step(layer, self.x[l], ws=self.ws, out=self.y, nnz=nnz[l])
-            binding.stack_glue(self.x[l], self.y, self.shifts[l], out=self.x[l + 1])
+            if not fused or l == len(self.layers) - 1:
+                binding.stack_glue(self.x[l], self.y, self.shifts[l], out=self.x[l + 1])
         return self.x[-1]

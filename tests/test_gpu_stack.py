@@ -94,3 +94,57 @@ def test_dense_stack_close_to_sparse(small_stack):
         b = st.as_dense().step(Xd[t]).float()
         # the predictor keeps ~99 % of the truly active neurons: outputs are close, not equal
         assert torch.linalg.norm(a - b) <= 0.25 * torch.linalg.norm(b)
+
+
+def test_glue_inside_the_step_gives_the_same_bits(small_stack):
+    """svdp_ffn_step_glued: x_out equals svdp_stack_glue's output and y, mask and list equal
+    svdp_ffn_step on it, bit for bit, for every batch size; the stack gives the same output with the glue
+    fused into the next layer's first kernel or launched on its own."""
+    layers, st, binding, torch = small_stack
+    L = st.layers[1]
+    d, D = L.d, L.D
+    g = torch.Generator(device="cuda").manual_seed(3)
+    for dt_layer in (L,):
+        for B in (1, 2, 3, 8):
+            xp = torch.randn(B, d, device="cuda", generator=g).to(torch.bfloat16)
+            yp = torch.randn(B, d, device="cuda", generator=g) * 0.7
+            shift = torch.randn(d, device="cuda", generator=g)
+            x_ref = torch.stack([binding.stack_glue(xp[b], yp[b], shift) for b in range(B)])
+            m1, m2 = (torch.zeros(D // 64, dtype=torch.int64, device="cuda") for _ in range(2))
+            i1, i2 = (torch.full((D,), -1, dtype=torch.int32, device="cuda") for _ in range(2))
+            n1, n2 = (torch.zeros(1, dtype=torch.int32, device="cuda") for _ in range(2))
+            y_ref = binding.ffn_step(dt_layer, x_ref, mask=m1, idx=i1, nnz=n1)
+            x_out = torch.zeros_like(xp)
+            y = binding.ffn_step_glued(dt_layer, xp, yp, shift, x_out, mask=m2, idx=i2, nnz=n2)
+            assert torch.equal(x_out, x_ref)
+            assert torch.equal(y, y_ref) and torch.equal(m1, m2) and n1.item() == n2.item()
+            assert torch.equal(i1[: n1.item()], i2[: n1.item()])
+            # y may alias y_prev
+            yp2 = yp.clone()
+            binding.ffn_step_glued(dt_layer, xp, yp2, shift, x_out, out=yp2)
+            assert torch.equal(yp2, y_ref)
+    Xd = binding.to_device(synth.timed_tokens(layers[0], 4), "bf16")
+    plain = st.with_glue_launches()
+    assert st.fused_glue and not plain.fused_glue
+    for t in range(4):
+        assert torch.equal(st.step(Xd[t]).clone(), plain.step(Xd[t]))
+
+
+def test_glued_step_fp32(oracle):
+    """The fp32 storage path of the fused glue against the oracle's glue and step."""
+    import torch
+    from paper_2603_14110_amd import binding
+
+    Ls = synth.make_layer(synth.workload("tiny"))
+    dev = binding.DeviceLayer.from_synth(Ls)
+    rng = np.random.default_rng(4)
+    d = Ls.spec.d
+    xp, yp, shift = (rng.standard_normal(d).astype(np.float32) for _ in range(3))
+    x_out = torch.zeros(1, d, device="cuda")
+    y = binding.ffn_step_glued(dev, torch.from_numpy(xp).cuda()[None], torch.from_numpy(yp).cuda()[None],
+                               torch.from_numpy(shift).cuda(), x_out)
+    x_or = oracle.stack_glue(xp, yp, shift)
+    assert np.allclose(x_out.cpu().numpy()[0], x_or, rtol=1e-5, atol=1e-6)
+    assert torch.equal(x_out[0], binding.stack_glue(torch.from_numpy(xp).cuda(), torch.from_numpy(yp).cuda(),
+                                                    torch.from_numpy(shift).cuda()))
+    assert torch.equal(y, binding.ffn_step(dev, x_out))
