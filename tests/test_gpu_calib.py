@@ -191,3 +191,45 @@ def test_stats_reject_fp32_layers(env):
     dev = binding.DeviceLayer.from_synth(L)
     with pytest.raises(binding.SvdpError):
         binding.calib_stats(dev, binding.to_device(synth.timed_tokens(L, 4), "f32"))
+
+
+def test_full_size_layer_as_benchmarked(env):
+    """The 7B-shaped layer with the calibration set bench.py --calibrate uses (2048 tokens, eta = 16,
+    sparsity level 0.9): statistics on sampled neurons against the oracle, then pointers, bias and
+    step count of the whole layer against the priority-queue loop on the GPU's statistics."""
+    binding, torch, calib = env
+    from paper_2603_14110_amd import synth
+
+    L = synth.load_or_make(synth.workload("7b"))
+    sp = L.spec
+    dev = binding.DeviceLayer.from_synth(L)
+    T, eta = 2048, 16
+    Xc = synth.make_tokens(sp, L.u, T, 1)
+    w, s = binding.calib_stats(dev, binding.to_device(Xc, sp.dtype))
+    need = binding.calib_need(0.9, sp.D, T)
+    b, k, steps, kend = binding.calib_bias(w, s, eta, need, want_kendall=True)
+    torch.cuda.synchronize()
+    wh, sh = w.cpu().numpy(), s.cpu().numpy()
+    # sampled neurons: first, last, tile borders of the contraction kernel, random ones
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([[0, 127, 128, sp.D - 129, sp.D - 1], rng.choice(sp.D, 40, replace=False)]))
+    Xf = synth.storage_to_f32(Xc, sp.dtype)
+    f = {n: L.f32(n)[rows] for n in ("W_gate", "W_up", "W_downT", "Q")}
+    s_or = calib.proxy_scores(f["Q"], L.f32("P").T, Xf)
+    smax = np.abs(sh).max(axis=0, keepdims=True)                     # per token, over all neurons
+    assert np.all(np.abs(sh[rows] - s_or) <= 2e-5 * smax)
+    w_or = calib.damage_weights(f["W_gate"], f["W_up"], f["W_downT"], Xf)
+    X64, Xa = Xf.astype(np.float64), np.abs(Xf.astype(np.float64))
+    gam = sp.d * 2.0 ** -24 / 4
+    g, u = f["W_gate"].astype(np.float64) @ X64.T, f["W_up"].astype(np.float64) @ X64.T
+    eg, eu = gam * (np.abs(f["W_gate"]).astype(np.float64) @ Xa.T), gam * (np.abs(f["W_up"]).astype(np.float64) @ Xa.T)
+    cn = np.sum(f["W_downT"].astype(np.float64) ** 2, axis=1)[:, None]
+    dz = eg * np.abs(u) + eu * np.maximum(g, 0) + eg * eu
+    bound = cn * (2 * np.abs(np.maximum(g, 0) * u) * dz + dz * dz) * 1.01 + 1e-5 * w_or
+    assert np.all(np.abs(wh[rows] - w_or) <= bound)
+    # the whole layer's calibration against the sequential loop on the same statistics
+    ref = calib.greedy_bias(wh, sh, need, eta)
+    assert np.array_equal(k.cpu().numpy(), ref["k"])
+    assert np.array_equal(b.cpu().numpy().view(np.uint32), ref["b"].view(np.uint32))
+    assert steps.item() == ref["steps"] and ref["count"] >= need
+    assert np.allclose(kend.cpu().numpy()[rows], calib.kendall_tau(wh[rows], sh[rows], eta), rtol=0, atol=2e-7)
