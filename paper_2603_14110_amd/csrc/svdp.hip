@@ -756,7 +756,7 @@ svdp_status svdp_calib_stats(const svdp_layer *layer, const void *X, int32_t T, 
     return hip_status(hipSuccess);
 }
 
-const char *svdp_version(void) { return "0.2"; }
+const char *svdp_version(void) { return "0.3"; }
 
 void svdp_set_step_mode(int32_t mode, int32_t spin_limit)
 {
