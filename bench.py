@@ -252,6 +252,18 @@ def measured_traffic(a):
         return None
 
 
+def gpu_clocks():
+    """Current clocks as rocm-smi reports them right after the timed runs (they cannot be pinned here)."""
+    import subprocess
+
+    try:
+        p = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+        card = next(iter(json.loads(p.stdout).values()))
+        return {k.split()[0]: str(v).strip("()") for k, v in card.items() if "clock speed" in k}
+    except Exception as e:          # absent tool, other output format: the benchmark line does not depend on it
+        return {"unavailable": type(e).__name__}
+
+
 def table4(a):
     """The protocol of the paper's executor table (Sec. 5.4): FFN only, predictor excluded, the same
     fixed sparsity on all three projections, speed-up over the dense FFN on the same GPU."""
@@ -449,6 +461,7 @@ def main():
     }
     if "cpu_baseline" in r:
         out["cpu_baseline"] = r["cpu_baseline"]
+    out["clocks"] = gpu_clocks()
     print(json.dumps(out))
 
 
