@@ -660,7 +660,7 @@ size_t svdp_calib_workspace_bytes(int32_t D, int32_t T, int32_t eta)
     if (D < 1 || T < 1 || T > CAL_MAX_T || eta < 1) return 0;
     const size_t MS = ((size_t)T + eta - 1) / eta;
     return align_up((size_t)D * MS * 4) + 2 * align_up((size_t)D * (MS + 1) * 4) + align_up((size_t)D * 4) +
-           align_up(sizeof(SelectState)) + align_up((size_t)SEL_BINS * 8);
+           align_up(sizeof(SelectState)) + align_up((size_t)SEL_BINS * 8) + 2 * align_up((size_t)D * 4);
 }
 
 svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
@@ -706,7 +706,12 @@ svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T
     hipLaunchKernelGGL((k_select_pick<7, false>), dim3(1), dim3(64), 0, st, state, hist);
     hipLaunchKernelGGL((k_select_hist<0, 7>), dim3(hb), dim3(256), 0, st, key, drop, D, MS, state, hist);
     hipLaunchKernelGGL((k_select_pick<0, false>), dim3(1), dim3(64), 0, st, state, hist);
-    hipLaunchKernelGGL(k_select_finish, dim3(1), dim3(SEL_THREADS), 0, st, key, drop, tauc, k0, D, T, eta, MS, state, b,
+    p += align_up((size_t)SEL_BINS * 8);
+    int32_t *lo = reinterpret_cast<int32_t *>(p);
+    p += align_up((size_t)D * 4);
+    int32_t *up = reinterpret_cast<int32_t *>(p);
+    hipLaunchKernelGGL(k_select_bounds, dim3((D + 255) / 256), dim3(256), 0, st, key, D, MS, state, lo, up);
+    hipLaunchKernelGGL(k_select_finish, dim3(1), dim3(SEL_THREADS), 0, st, lo, up, drop, tauc, k0, D, T, eta, MS, state, b,
                        k, steps);
     return hip_status(hipSuccess);
 }

@@ -9,11 +9,12 @@
 // costs (a step cheaper than its predecessor is taken right after it), so the
 // whole sequence is all steps sorted by (running-max cost, neuron, step).  Two
 // kernels follow from it:
-//   k_calib_sort   one block per neuron: bitonic sort of the samples by score in
-//                  LDS (ties keep sample order), first positive weight, step
-//                  costs (fp32, left to right), their running maxima, and for
-//                  every step the number of dropped samples and the threshold
-//                  it would set; optionally the Kendall check of App. A.
+//   k_calib_sort   one block per neuron: the samples from the first positive weight
+//                  on (in the order by score, ties by sample index) are sorted
+//                  in LDS, the ones below only counted; step costs (fp32, left
+//                  to right), their running maxima, and for every step the
+//                  number of dropped samples and the threshold it would set;
+//                  optionally the Kendall check of App. A.
 //   k_select_*     the cost level at which the required number of pairs is first
 //                  reached, by a radix select over the keys' bit patterns
 //                  (four digit passes, integer atomics); then one block takes
@@ -42,29 +43,67 @@ __device__ __forceinline__ uint32_t ordered_bits(float v)
 //   drop [D][MS + 1] number of samples with s <= tau after 0, 1, 2, ... steps
 //   tauc [D][MS + 1] the threshold after 0, 1, 2, ... steps
 //   k0   [D]         the starting pointer (1-based count)
-// Dynamic LDS: n2*8 (sort keys) + 2*T*4 (sorted s, w) + 2*(MS+1)*4 bytes, n2 = T rounded up to a power of two.
+// Only the part of the order that the algorithm walks is sorted: everything below the first sample
+// with a positive weight (in the order by score, then sample index) is merely counted -- those
+// samples have zero weight and are dropped from the start -- and the rest, the "tail", typically a
+// tenth of the samples of a sparse layer, goes through a bitonic sort sized to it.
+// Dynamic LDS: n2*8 (sort keys) + 2*T*4 (sorted tail: s, w) + 2*(MS+1)*4 bytes, n2 = T rounded up to a power of two.
 __global__ __launch_bounds__(CAL_THREADS) void k_calib_sort(const float *__restrict__ w, const float *__restrict__ s,
-                                                            int T, int n2, int eta, int MS, float *__restrict__ key,
-                                                            int32_t *__restrict__ drop, float *__restrict__ tauc,
-                                                            int32_t *__restrict__ k0_out, float *__restrict__ kendall)
+                                                            int T, int n2max, int eta, int MS,
+                                                            float *__restrict__ key, int32_t *__restrict__ drop,
+                                                            float *__restrict__ tauc, int32_t *__restrict__ k0_out,
+                                                            float *__restrict__ kendall)
 {
     extern __shared__ unsigned long long smem64[];
-    unsigned long long *sk = smem64;                               // [n2]
-    float *ss = reinterpret_cast<float *>(sk + n2);                // [T] sorted scores
+    unsigned long long *sk = smem64;                               // [n2max]
+    float *ss = reinterpret_cast<float *>(sk + n2max);             // [T] scores of the tail, sorted
     float *ww = ss + T;                                            // [T] weights in that order
     float *cost = ww + T;                                          // [MS + 1]
     float *scan = cost + (MS + 1);                                 // [MS + 1]
-    __shared__ int first_pos;
-    __shared__ int kd_total;
+    __shared__ unsigned long long kmin_sh;                         // smallest (score, sample) key with a positive weight
+    __shared__ unsigned long long kmax_sh;                         // largest (score, sample) key: the last sample in sorted order
+    __shared__ int below_sh, fill_sh, kd_total;
     const int i = blockIdx.x, tid = threadIdx.x;
     const float *si = s + (size_t)i * T, *wi = w + (size_t)i * T;
+    auto key_of = [&](int t) { return ((unsigned long long)ordered_bits(si[t]) << 32) | (unsigned)t; };
 
-    for (int t = tid; t < n2; t += CAL_THREADS)
-        sk[t] = t < T ? ((unsigned long long)ordered_bits(si[t]) << 32) | (unsigned)t : ~0ull;
     if (tid == 0) {
-        first_pos = T;
+        kmin_sh = ~0ull;
+        kmax_sh = 0ull;
+        below_sh = 0;
+        fill_sh = 0;
         kd_total = 0;
     }
+    __syncthreads();
+    {
+        unsigned long long kmin = ~0ull;
+        unsigned long long kmax = 0ull;
+        for (int t = tid; t < T; t += CAL_THREADS) {
+            const unsigned long long k = key_of(t);
+            if (wi[t] > 0.f && k < kmin) kmin = k;
+            if (k > kmax) kmax = k;
+        }
+        if (kmin != ~0ull) atomicMin(&kmin_sh, kmin);
+        atomicMax(&kmax_sh, kmax);
+    }
+    __syncthreads();
+    const unsigned long long kmin = kmin_sh;
+    // the tail: samples at or above the first positive one; the rest is counted
+    {
+        int below = 0;
+        for (int t = tid; t < T; t += CAL_THREADS) {
+            const unsigned long long k = key_of(t);
+            if (k < kmin) ++below;
+            else sk[atomicAdd(&fill_sh, 1)] = k;                   // any order: sorted next
+        }
+        if (below) atomicAdd(&below_sh, below);
+    }
+    __syncthreads();
+    const int nb = below_sh;                                       // samples below the tail (T if no weight is positive)
+    const int ntail = T - nb;
+    int n2 = 1;
+    while (n2 < ntail) n2 <<= 1;
+    for (int t = ntail + tid; t < n2; t += CAL_THREADS) sk[t] = ~0ull;
     __syncthreads();
     for (int k = 2; k <= n2; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
@@ -82,20 +121,19 @@ __global__ __launch_bounds__(CAL_THREADS) void k_calib_sort(const float *__restr
             __syncthreads();
         }
     }
-    for (int p = tid; p < T; p += CAL_THREADS) {
+    for (int p = tid; p < ntail; p += CAL_THREADS) {
         const int t = (int)(sk[p] & 0xffffffffu);
-        const float wv = wi[t];
         ss[p] = si[t];
-        ww[p] = wv;
-        if (wv > 0.f) atomicMin(&first_pos, p);
+        ww[p] = wi[t];
     }
     __syncthreads();
-    const int k0 = first_pos < T ? first_pos + 1 : T;              // min{k : w_(k) > 0}, or T if there is none
+    // sorted position q of the whole sample = tail position q - nb; the first positive weight is tail position 0
+    const int k0 = ntail > 0 ? nb + 1 : T;                         // min{k : w_(k) > 0}, or T if there is none
     const int M = (T - k0 + eta - 1) / eta;                        // steps this neuron can take
 
     // step costs C(k + eta) - C(k), fp32 left to right; the last step may be short (the listing's padding)
     for (int j = tid; j < M; j += CAL_THREADS) {
-        const int lo = k0 + j * eta, hi = min(lo + eta, T);
+        const int lo = k0 - nb + j * eta, hi = min(lo + eta, ntail);
         float c = 0.f;
         for (int p = lo; p < hi; ++p) c += ww[p];
         cost[j] = c;
@@ -111,20 +149,26 @@ __global__ __launch_bounds__(CAL_THREADS) void k_calib_sort(const float *__restr
         dst = tmp;
     }
     for (int j = tid; j < MS; j += CAL_THREADS) key[(size_t)i * MS + j] = j < M ? src[j] : __builtin_inff();
-    // thresholds and dropped counts after j steps: k = min(k0 + j*eta, T), tau = s_(k), #{s <= tau}
+    // thresholds and dropped counts after j steps: k = min(k0 + j*eta, T), tau = s_(k), #{s <= tau};
+    // every sample below the tail has a score <= tau
     for (int j = tid; j <= MS; j += CAL_THREADS) {
         int dj = 0;
         float tj = 0.f;
         if (j <= M) {
-            const int k = min(k0 + j * eta, T);
-            tj = ss[k - 1];
-            int lo = k, hi = T;                                     // first position whose score exceeds tau
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (ss[mid] <= tj) lo = mid + 1;
-                else hi = mid;
+            if (ntail == 0) {                                       // nothing ever active: all dropped, tau = the last score
+                tj = si[(int)(kmax_sh & 0xffffffffu)];
+                dj = T;
+            } else {
+                const int k = min(k0 + j * eta, T) - nb;            // tail count, >= 1
+                tj = ss[k - 1];
+                int lo = k, hi = ntail;                             // first tail position whose score exceeds tau
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (ss[mid] <= tj) lo = mid + 1;
+                    else hi = mid;
+                }
+                dj = nb + lo;
             }
-            dj = lo;
         }
         drop[(size_t)i * (MS + 1) + j] = dj;
         tauc[(size_t)i * (MS + 1) + j] = tj;
@@ -132,13 +176,14 @@ __global__ __launch_bounds__(CAL_THREADS) void k_calib_sort(const float *__restr
     if (tid == 0) k0_out[i] = k0;
 
     if (kendall != nullptr) {
-        // App. A: non-overlapping eta-step sums over the whole sorted sample, discordant pairs m1 < m2
+        // App. A: non-overlapping eta-step sums over the whole sorted sample (zero below the tail),
+        // discordant pairs m1 < m2
         const int MK = T / eta;
         __syncthreads();                                            // cost/scan are free again
         float *S = cost;                                            // MK <= MS entries
         for (int m = tid; m < MK; m += CAL_THREADS) {
             float c = 0.f;
-            for (int p = m * eta; p < (m + 1) * eta; ++p) c += ww[p];
+            for (int q = max(m * eta, nb); q < (m + 1) * eta; ++q) c += ww[q - nb];
             S[m] = c;
         }
         __syncthreads();
@@ -241,35 +286,66 @@ __global__ __launch_bounds__(256) void k_select_hist(const float *__restrict__ k
         if (lh[q] != 0) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[q]), (unsigned long long)lh[q]);
 }
 
-// Picks the digit, updates the state and clears the histogram for the next digit.
+// Picks the digit, updates the state and clears the histogram for the next digit.  One wave:
+// lane l owns bins 4l .. 4l+3, a shuffle scan gives the running sums.
 template <int SHIFT, bool FIRST>
 __global__ __launch_bounds__(64) void k_select_pick(SelectState *__restrict__ st, long long *__restrict__ hist)
 {
-    if (threadIdx.x != 0) return;
-    if (st->reachable != 0) {
-        long long run = 0;
-        int digit = -1;
-        const long long missing = st->missing;
-        for (int q = 0; q < SEL_BINS; ++q) {
-            if (digit < 0 && run + hist[q] >= missing) {
-                digit = q;
+    const int lane = threadIdx.x;
+    long long h[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        h[q] = hist[4 * lane + q];
+        hist[4 * lane + q] = 0;
+    }
+    if (st->reachable == 0) return;
+    const long long missing = st->missing;
+    const long long mine = h[0] + h[1] + h[2] + h[3];
+    long long inc = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
+    }
+    const long long before = inc - mine;
+    const bool here = before < missing && inc >= missing;           // at most one lane
+    const unsigned long long who = __ballot(here);
+    if (who == 0ull) {
+        if (lane == 0) st->reachable = 0;       // only on the first digit: every finite step together falls short
+        return;
+    }
+    if (here) {
+        long long run = before;
+        int digit = 0;
+        for (int q = 0; q < 4; ++q) {
+            if (run + h[q] >= missing) {
+                digit = 4 * lane + q;
                 break;
             }
-            run += hist[q];
+            run += h[q];
         }
-        if (digit < 0) {
-            st->reachable = 0;                  // only on the first digit: every finite step together falls short
-        } else {
-            st->missing = missing - run;        // still to be found among the steps with this digit
-            st->prefix |= (uint32_t)digit << SHIFT;
-        }
+        st->missing = missing - run;            // still to be found among the steps with this digit
+        st->prefix |= (uint32_t)digit << SHIFT;
     }
-    for (int q = 0; q < SEL_BINS; ++q) hist[q] = 0;
 }
 
-// With the level known: steps strictly below it are all taken; those at the level in neuron order
-// until the missing pairs are found; writes b = -tau, the pointers and the number of steps.
-__global__ __launch_bounds__(SEL_THREADS) void k_select_finish(const float *__restrict__ key,
+// With the level known, per neuron: the number of its steps strictly below the level and up to it.
+__global__ __launch_bounds__(256) void k_select_bounds(const float *__restrict__ key, int D, int MS,
+                                                       const SelectState *__restrict__ st,
+                                                       int32_t *__restrict__ lo_out, int32_t *__restrict__ up_out)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= D) return;
+    const float lv = __uint_as_float(st->reachable != 0 ? st->prefix : SEL_TOP);
+    const float *ki = key + (size_t)i * MS;
+    lo_out[i] = steps_below<false>(ki, MS, lv);
+    up_out[i] = steps_below<true>(ki, MS, lv);
+}
+
+// Steps strictly below the level are all taken; those at the level in neuron order until the
+// missing pairs are found; writes b = -tau, the pointers and the number of steps.  One block.
+__global__ __launch_bounds__(SEL_THREADS) void k_select_finish(const int32_t *__restrict__ lo_in,
+                                                               const int32_t *__restrict__ up_in,
                                                                const int32_t *__restrict__ drop,
                                                                const float *__restrict__ tauc,
                                                                const int32_t *__restrict__ k0, int D, int T, int eta,
@@ -284,7 +360,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_finish(const float *__re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool at_start = st->at_start != 0;
     const bool reachable = st->reachable != 0;
-    const float lv = __uint_as_float(reachable ? st->prefix : SEL_TOP);
     const long long missing = st->missing;                          // among the steps at the level
     if (tid == 0) {
         star = D;
@@ -296,9 +371,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_finish(const float *__re
         const int i = i0 + tid;
         long long gain = 0;
         if (i < D) {
-            const float *ki = key + (size_t)i * MS;
             const int32_t *di = drop + (size_t)i * (MS + 1);
-            gain = (long long)di[steps_below<true>(ki, MS, lv)] - di[steps_below<false>(ki, MS, lv)];
+            gain = (long long)di[up_in[i]] - di[lo_in[i]];
         }
         long long inc = gain;                                       // inclusive scan inside the wave
 #pragma unroll
@@ -326,17 +400,14 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select_finish(const float *__re
     const long long sb = star_before;
     long long taken = 0;
     for (int i = tid; i < D; i += SEL_THREADS) {
-        const float *ki = key + (size_t)i * MS;
         const int32_t *di = drop + (size_t)i * (MS + 1);
         int J;
         if (at_start) {
             J = 0;
-        } else if (!reachable) {
-            J = steps_below<true>(ki, MS, lv);                      // every finite step: the target cannot be met
-        } else if (i < istar) {
-            J = steps_below<true>(ki, MS, lv);
+        } else if (!reachable || i < istar) {
+            J = up_in[i];                                           // unreachable target: every finite step
         } else {
-            J = steps_below<false>(ki, MS, lv);
+            J = lo_in[i];
             if (i == istar) {
                 long long c = sb;
                 while (c < missing) {                               // its steps at the level, one at a time
