@@ -180,3 +180,44 @@ def test_engine_selection_and_determinism(env):
     y2 = binding.ffn_step(c2.dev, c2.Xd).clone()
     binding.set_engine(binding.ENGINE_AUTO)
     assert torch.equal(y1, y2)
+
+
+def test_matrix_engine_under_graph_replay(env):
+    """The matrix-core kernels captured in a HIP graph (as bench.py runs them): every replay, with eager work
+    in between, reproduces the eager result bit for bit; so do the sequential-pipeline kernel and calibration-free
+    reruns on the same workspace."""
+    binding, torch, oracle = env
+    c = RandomLayer(binding, torch, 21, 1024, 6144, 64, 8)
+    seq = c.dev.with_flags(binding.FLAG_REVALIDATE)
+    ws = c.dev.workspace(8)
+    xin = torch.zeros_like(c.Xd)
+    outs = {k: torch.zeros(8, c.d, device="cuda") for k in ("step", "dense", "seq")}
+
+    def work():
+        binding.ffn_step(c.dev, xin, ws=ws, out=outs["step"])
+        binding.dense_ffn(c.dev, xin, ws=ws, out=outs["dense"])
+        binding.ffn_step(seq, xin, ws=ws, out=outs["seq"])
+
+    variants = [c.Xd, torch.flip(c.Xd, dims=[0]), c.Xd * 0.5]
+    eager = []
+    for v in variants:
+        xin.copy_(v)
+        work()
+        torch.cuda.synchronize()
+        eager.append({k: t.clone() for k, t in outs.items()})
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        work()
+        s.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            work()
+    for rnd in range(3):
+        for v, ref in zip(variants, eager):
+            xin.copy_(v)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for k in outs:
+                assert torch.equal(outs[k], ref[k]), (rnd, k)
+            binding.ffn_step(c.dev, c.Xd[:3])                       # eager work between replays
