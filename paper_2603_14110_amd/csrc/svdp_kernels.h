@@ -19,7 +19,7 @@ constexpr int ROWS_WAVES = ROWS_THREADS / 64;
 constexpr int ROWS_UB = 4;           // k_rows: rows of W_downT fetched together (chunk padded to this)
 constexpr int SCAN_THREADS = 1024;   // k_compact_scan block
 constexpr int RED_COLS = 8;          // k_reduce_y: float4 columns per block (one 128-byte line per partial row)
-constexpr int RED_SEGS = 128;        // k_reduce_y: segments of the partial list per block
+constexpr int RED_SEGS = 64;         // k_reduce_y: segments of the partial list per block
 
 // Sum over j < d of (x[j] + y[j])^2 by a block of 256 threads in a fixed order (a thread takes the
 // 16-byte vectors t, t + 256, ... of x in ascending order, then the lanes of a wave, then the four
