@@ -77,45 +77,81 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
         for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
     const bool drelu = (flags & 1u) != 0;
 
-    // ---- phase G: gate, then up only where the gate is positive for some token ----
-    auto row_dot = [&](const W *rowp, float (&acc)[NB]) {
+    // ---- phase G: gate, then up only where the gate is positive for some token.  A wave works on two
+    // rows at a time (q and q + ROWS_WAVES) so that twice the loads are in flight ----
+    auto row_dot2 = [&](const W *rowa, const W *rowb, bool has_b, float (&acca)[NB], float (&accb)[NB]) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[b] = 0.f;
+        for (int b = 0; b < NB; ++b) acca[b] = accb[b] = 0.f;
         const int nfull = nvec / (64 * UG);
         for (int it = 0; it < nfull; ++it) {
-            uint4 rw[UG];
+            uint4 ra[UG], rb[UG];
 #pragma unroll
-            for (int k = 0; k < UG; ++k) rw[k] = load_raw(rowp + (size_t)(lane + (it * UG + k) * 64) * VEC);
+            for (int k = 0; k < UG; ++k) {
+                ra[k] = load_raw(rowa + (size_t)(lane + (it * UG + k) * 64) * VEC);
+                if (has_b) rb[k] = load_raw(rowb + (size_t)(lane + (it * UG + k) * 64) * VEC);
+            }
 #pragma unroll
             for (int k = 0; k < UG; ++k) {
                 const int v = lane + (it * UG + k) * 64;
 #pragma unroll
-                for (int b = 0; b < NB; ++b) acc[b] = dot_raw(rw[k], xraw[b * nvec + v], acc[b], (const W *)nullptr);
+                for (int b = 0; b < NB; ++b) {
+                    const uint4 xv = xraw[b * nvec + v];
+                    acca[b] = dot_raw(ra[k], xv, acca[b], (const W *)nullptr);
+                    if (has_b) accb[b] = dot_raw(rb[k], xv, accb[b], (const W *)nullptr);
+                }
             }
         }
         for (int v = lane + nfull * UG * 64; v < nvec; v += 64) {
-            const uint4 rw = load_raw(rowp + (size_t)v * VEC);
+            const uint4 ra = load_raw(rowa + (size_t)v * VEC);
+            uint4 rb = ra;
+            if (has_b) rb = load_raw(rowb + (size_t)v * VEC);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) acc[b] = dot_raw(rw, xraw[b * nvec + v], acc[b], (const W *)nullptr);
-        }
-#pragma unroll
-        for (int b = 0; b < NB; ++b) acc[b] = wave_sum(acc[b]);
-    };
-    for (int q = wave; q < cnt; q += ROWS_WAVES) {
-        const size_t row = (size_t)lidx[q];
-        float g[NB], u[NB];
-        row_dot(Wg + row * d, g);
-        bool alive = false;
-#pragma unroll
-        for (int b = 0; b < NB; ++b) alive = alive || (b < B && g[b] > 0.f);
-        if (alive) {                                             // uniform over the wave: g is a wave sum
-            row_dot(Wu + row * d, u);
-            if (lane == 0) {
-#pragma unroll
-                for (int b = 0; b < NB; ++b) hs[b * max_chunk + q] = fmaxf(g[b], 0.f) * (drelu ? fmaxf(u[b], 0.f) : u[b]);
+            for (int b = 0; b < NB; ++b) {
+                const uint4 xv = xraw[b * nvec + v];
+                acca[b] = dot_raw(ra, xv, acca[b], (const W *)nullptr);
+                if (has_b) accb[b] = dot_raw(rb, xv, accb[b], (const W *)nullptr);
             }
         }
-        if (lane == 0) srow[q] = alive ? 1 : 0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            acca[b] = wave_sum(acca[b]);
+            accb[b] = wave_sum(accb[b]);
+        }
+    };
+    for (int q = wave; q < cnt; q += 2 * ROWS_WAVES) {
+        const int q2 = q + ROWS_WAVES;
+        const bool two = q2 < cnt;                               // uniform over the wave
+        const size_t rowa = (size_t)lidx[q], rowb = (size_t)lidx[two ? q2 : q];
+        float ga[NB], gb[NB], ua[NB], ub[NB];
+        row_dot2(Wg + rowa * d, Wg + rowb * d, two, ga, gb);
+        bool alive_a = false, alive_b = false;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            alive_a = alive_a || (b < B && ga[b] > 0.f);
+            alive_b = alive_b || (two && b < B && gb[b] > 0.f);
+        }
+        // both tests are uniform over the wave: the gates are wave sums
+        if (alive_a && alive_b) {
+            row_dot2(Wu + rowa * d, Wu + rowb * d, true, ua, ub);
+        } else if (alive_a) {
+            row_dot2(Wu + rowa * d, Wu + rowa * d, false, ua, ub);
+        } else if (alive_b) {
+            row_dot2(Wu + rowb * d, Wu + rowb * d, false, ub, ua);
+        }
+        if (lane == 0) {
+            if (alive_a) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    hs[b * max_chunk + q] = fmaxf(ga[b], 0.f) * (drelu ? fmaxf(ua[b], 0.f) : ua[b]);
+            }
+            if (alive_b) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    hs[b * max_chunk + q2] = fmaxf(gb[b], 0.f) * (drelu ? fmaxf(ub[b], 0.f) : ub[b]);
+            }
+            srow[q] = alive_a ? 1 : 0;
+            if (two) srow[q2] = alive_b ? 1 : 0;
+        }
     }
     __syncthreads();
 
