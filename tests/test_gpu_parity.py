@@ -404,3 +404,19 @@ def test_full_size_sampled_tokens(env, name, over, B):
         step_check(env, c, B, t0)
     y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
     parity.check_y(y, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B]), c.spec.dtype)
+
+
+def test_full_size_sequential_pipeline_weak_predictor(env):
+    """7B shape with a rank-32 predictor (over-predicts about 4x), as `bench.py --rank 32 --flags 2` runs it:
+    the sequential pipeline against the oracle on the predictor's own list, and bit for bit against the
+    parallel pipeline."""
+    binding, torch, oracle = env
+    c = get_case(env, "7b", n_tok=64, r=32)
+    seq = c.dev.with_flags(binding.FLAG_REVALIDATE)
+    dens = []
+    for B, t0 in ((1, 0), (1, 9), (2, 16), (4, 24)):
+        lst, y = step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE, modes=(0,))
+        dens.append(lst.size / c.spec.D)
+        assert torch.equal(y, binding.ffn_step(c.dev, c.Xd[t0:t0 + B]))
+        assert torch.equal(binding.dense_ffn(seq, c.Xd[t0:t0 + B]), binding.dense_ffn(c.dev, c.Xd[t0:t0 + B]))
+    assert np.mean(dens) > 0.2          # the weak predictor keeps far more than the ~10 % that are active
