@@ -120,3 +120,14 @@ def test_binding_fails_loudly_without_library(svdp, monkeypatch):
     monkeypatch.setattr(svdp, "LIB_PATH", "/nonexistent/libsvdp.so")
     with pytest.raises(svdp.SvdpError):
         svdp.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N > 1 says so and exits without touching a device."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert p.returncode != 0 and "ONE GPU" in p.stderr and p.stdout.strip() == ""
