@@ -46,7 +46,7 @@ def parse():
                     help="--workload stack: the glue between layers as launches of its own (default: inside the "
                          "next layer's first kernel)")
     ap.add_argument("--engine", default="auto", choices=["auto", "vector", "matrix"],
-                    help="arithmetic units of the batch-sensitive kernels (svdp_set_engine)")
+                    help="arithmetic units of the batch-sensitive kernels (SVDP_FLAG_ENGINE_* of the layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
@@ -138,7 +138,8 @@ def run_layer(a, torch, np, binding, cost, synth):
     def rows_only(k):          # the dominant kernel by itself, on the mask words the steps produced
         binding.active_rows(copies[k % len(copies)], Xd[k], MASK[k], ws=ws)
 
-    plain = [c.with_flags(0) for c in copies]        # the dense baseline never takes the pipeline flags
+    engine_bits = a.flags & (binding.FLAG_ENGINE_VECTOR | binding.FLAG_ENGINE_MATRIX)
+    plain = [c.with_flags(engine_bits) for c in copies]     # the dense baseline never takes the pipeline flags
 
     def dense_step(k):
         binding.dense_ffn(plain[k % len(plain)], Xd[k], ws=ws, out=Y[k])
@@ -385,8 +386,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     binding.lib()
-    binding.set_engine({"auto": binding.ENGINE_AUTO, "vector": binding.ENGINE_VECTOR,
-                             "matrix": binding.ENGINE_MATRIX}[a.engine])
+    a.flags |= {"auto": 0, "vector": binding.FLAG_ENGINE_VECTOR, "matrix": binding.FLAG_ENGINE_MATRIX}[a.engine]
     if a.table4:
         table4(a)
         return

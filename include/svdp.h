@@ -17,9 +17,10 @@
  *    enqueued and a status other than SVDP_OK is returned;
  *  - `ws` is a device scratch buffer of at least svdp_workspace_bytes() bytes,
  *    256-byte aligned, owned by the caller; its contents are undefined between
- *    calls; two calls that may overlap in time need distinct workspaces (at
- *    most 64 distinct workspace addresses per process get the persistent step
- *    kernel, further ones use the kernel sequence);
+ *    calls; two calls that may overlap in time need distinct workspaces;
+ *  - the library keeps no mutable state between calls: everything a call does
+ *    follows from its arguments, so calls on different streams and from
+ *    different host threads are independent (given distinct workspaces);
  *  - B is the number of tokens decoded together, 1 <= B <= SVDP_MAX_BATCH; all
  *    tokens of a batch share ONE mask (the union of their masks) and one index
  *    list, and every token is computed exactly over that list;
@@ -29,7 +30,10 @@
  *
  * Shape limits (else SVDP_ERR_UNSUPPORTED): D % 64 == 0, and with
  * e = 4 (fp32) or 8 (bf16) elements per 16 bytes: d % e == 0, r % e == 0,
- * r <= 2048, d <= 16384.  Every matrix pointer must be 16-byte aligned.
+ * r <= 2048, d <= 16384; the tokens of a batch must also fit the 160 KB of
+ * local memory of a compute unit next to a kernel's scratch (B * d storage
+ * elements; svdp_workspace_bytes returns 0 for a shape and batch that do not).
+ * Every matrix pointer must be 16-byte aligned.
  */
 #ifndef SVDP_H
 #define SVDP_H
@@ -66,10 +70,28 @@ enum {
      * is read.  The output is unchanged (such a neuron contributes exactly zero);
      * what changes is the bytes read: d*w per listed neuron for the gate, 2*d*w more
      * only for those that survive.  Pays when the predictor over-predicts (low rank,
-     * cautious bias); costs one more dependent fetch per row otherwise.  In the
-     * default launch organisation a dedicated row kernel runs (vector units); the
-     * optional organisations skip the W_down row only.                             */
-    SVDP_FLAG_REVALIDATE = 2u
+     * cautious bias); costs one more dependent fetch per row otherwise.  A dedicated
+     * row kernel runs (vector units).                                                */
+    SVDP_FLAG_REVALIDATE = 2u,
+    /* Which arithmetic units the batch-sensitive kernels use.  The paper's App. C gives a
+     * row-at-a-time kernel (Alg. 3) and a gather-then-dense-contraction form (Alg. 4); its
+     * Sec. 6 notes that batching lowers the sparsity the first can exploit.
+     *  neither flag (default): per kernel and batch capacity, whichever was measured faster on
+     *      MI355X: matrix cores for the scores from 3 tokens and for the rows from 5 tokens,
+     *      vector units below.
+     *  SVDP_FLAG_ENGINE_VECTOR: fp32 vector arithmetic everywhere (any dtype, batch, flags).
+     *  SVDP_FLAG_ENGINE_MATRIX: matrix cores wherever a kernel for them exists:
+     *      - rows (gate, up, down over the list): taken 16 at a time as MFMA tiles straight
+     *        from their place in the weight matrices (no gathered copy), bf16 x bf16 -> fp32
+     *        for gate and up, fp32 outer products for the down projection; needs bf16 storage,
+     *        d a multiple of 512 and no SVDP_FLAG_REVALIDATE;
+     *      - scores (t Q^T + b): bf16 MFMAs with t split into three bf16 terms (exact to fp32);
+     *        needs bf16 storage, r a multiple of 32, r <= 512.
+     *      Layers that do not qualify use the vector kernels.
+     * Both engines give the same mask and list (up to scores within rounding of zero) and a y
+     * that agrees to fp32 rounding (sums are cut differently).  Setting both is an error.     */
+    SVDP_FLAG_ENGINE_VECTOR = 4u,
+    SVDP_FLAG_ENGINE_MATRIX = 8u
 };
 
 /* One FFN layer with its predictor.  All pointers are device pointers.
@@ -105,16 +127,18 @@ svdp_status svdp_predict(const svdp_layer *layer, const void *x, int32_t B,
  * s: device [B][D] fp32.  mask: device [D/64] 64-bit words, bit j of word k is
  * neuron 64k+j, fully written.  idx: device [D] int32, receives the active neurons
  * in ascending order in idx[0..nnz), the rest is left untouched.  nnz: device
- * [1] int32.  Needs no workspace.                                               */
+ * [1] int32.  ws, ws_bytes: accepted for uniformity with the other calls; this
+ * call needs no scratch, NULL and 0 are fine.                                   */
 svdp_status svdp_compact(const float *s, int32_t B, int32_t D, uint64_t *mask,
-                         int32_t *idx, int32_t *nnz, void *stream);
+                         int32_t *idx, int32_t *nnz, void *ws, size_t ws_bytes, void *stream);
 
 /* Sparse ReGLU FFN over an index list (Sec. 3; Alg. 3's three kernels / Alg. 4):
  *   y[t][:] = sum_{n < nnz} ReLU(W_gate[i_n]·x[t]) * (W_up[i_n]·x[t]) * W_downT[i_n][:],
  * i_n = idx[n].  Only the listed rows of the three matrices are read.
  * idx: device int32, entries in [0, D), ascending not required but duplicates
- * are summed twice.  nnz: device [1] int32 with 0 <= *nnz <= D (read on the
- * device, never on the host).  y: device [B][d] fp32, fully written (zeros
+ * are summed twice; an entry outside [0, D) is skipped on the device (it
+ * contributes nothing and no row is read out of bounds).  nnz: device [1] int32,
+ * clamped on the device to 0 <= *nnz <= D (never read on the host).  y: device [B][d] fp32, fully written (zeros
  * when *nnz == 0).                                                              */
 svdp_status svdp_sparse_ffn(const svdp_layer *layer, const void *x, int32_t B,
                             const int32_t *idx, const int32_t *nnz, float *y,
@@ -141,51 +165,6 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
  * or svdp_ffn_step.                                                                          */
 svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask,
                              void *ws, size_t ws_bytes, void *stream);
-
-/* How the launches are organised (process-wide; call it while nothing is in flight).
- *  SVDP_STEP_SEQUENCE      (default) ordinary launches only: svdp_ffn_step is four kernels
- *                          (x P tiles, scores and mask words, rows -> partial y, sum of the
- *                          partials); svdp_sparse_ffn / svdp_dense_ffn are the last two.
- *  SVDP_STEP_MERGED_REDUCE as above, but the row kernel also sums the partial y's: its
- *                          blocks hand them over through global memory and a bounded wait
- *                          instead of a kernel boundary.
- *  SVDP_STEP_PERSISTENT    svdp_ffn_step as ONE persistent launch, one block per compute unit,
- *                          all four stages handed over that way.
- * The last two were measured slower than the sequence on MI355X (a kernel boundary is the
- * cheapest chip-wide hand-over there) and are kept as options.  They need every block of the
- * launch resident at once, so the GPU must not be shared with other work while they run;
- * shapes or devices that cannot guarantee it fall back to SVDP_STEP_SEQUENCE by themselves.
- * All modes give the same mask and index list; y agrees to rounding (partial sums are cut
- * differently).  spin_limit > 0 sets the number of polls after which a wait gives up (the
- * call then finishes with undefined output and the timeout is recorded).                    */
-typedef enum { SVDP_STEP_SEQUENCE = 0, SVDP_STEP_PERSISTENT = 1, SVDP_STEP_MERGED_REDUCE = 2 } svdp_step_mode;
-void svdp_set_step_mode(int32_t mode, int32_t spin_limit);
-
-/* Which arithmetic units the batch-sensitive kernels use (process-wide; call it while nothing
- * is in flight).  The paper's App. C gives a row-at-a-time kernel (Alg. 3) and a
- * gather-then-dense-contraction form (Alg. 4); its Sec. 6 notes that batching lowers the
- * sparsity the first can exploit.
- *  SVDP_ENGINE_AUTO   (default) per kernel and batch capacity, whichever was measured faster on
- *                     MI355X: matrix cores for the scores from 3 tokens and for the rows from
- *                     5 tokens, vector units below.
- *  SVDP_ENGINE_VECTOR fp32 vector arithmetic everywhere (any dtype, batch, flags).
- *  SVDP_ENGINE_MATRIX matrix cores wherever a kernel for them exists:
- *                     - rows (gate, up, down over the list): taken 16 at a time as MFMA tiles
- *                       straight from their place in the weight matrices (no gathered copy),
- *                       bf16 x bf16 -> fp32 for gate and up, fp32 outer products for the down
- *                       projection; needs bf16 storage, d a multiple of 512 and no
- *                       SVDP_FLAG_REVALIDATE;
- *                     - scores (t Q^T + b): bf16 MFMAs with t split into three bf16 terms
- *                       (exact to fp32); needs bf16 storage, r a multiple of 32, r <= 512.
- *                     Layers that do not qualify use the vector kernels whatever is set here.
- * Both give the same mask and list (up to scores within rounding of zero) and a y that agrees
- * to fp32 rounding (sums are cut differently).  Applies to SVDP_STEP_SEQUENCE only.          */
-typedef enum { SVDP_ENGINE_AUTO = 0, SVDP_ENGINE_VECTOR = 1, SVDP_ENGINE_MATRIX = 2 } svdp_engine;
-void svdp_set_engine(int32_t engine);
-
-/* Number of workspaces on which a launch gave up waiting since the last
- * call; clears the record.  Synchronises the device: not for use under capture. */
-svdp_status svdp_step_timeouts(int32_t *count);
 
 /* Glue between stacked layers used by the stacked benchmark (not from the
  * paper): v = x + y; x_next = v / sqrt(mean(v^2) + eps) + shift, rounded to
@@ -217,6 +196,11 @@ svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift,
  * Asynchronous on `stream`, no allocation, no host read-back.                                     */
 size_t svdp_calib_workspace_bytes(int32_t D, int32_t T, int32_t eta);
 
+/* The integer `need` of svdp_calib_bias for a sparsity level sp of Alg. 2 ("while the sparsity is below
+ * s"): the smallest integer n with n >= sp * D * T, the product taken in double precision from left to
+ * right, clamped to [0, D * T].  Host-only, pure.  Returns -1 for D < 1, T < 1 or sp not a number.     */
+int64_t svdp_calib_need(double sparsity, int32_t D, int32_t T);
+
 /* The statistics svdp_calib_bias consumes, for T calibration tokens X [T][d] (device, in the
  * layer's storage type): w [D][T] and s [D][T] as defined above, with A B x evaluated the way
  * the runtime predictor does, (x P) Q^T in fp32 (the layer's bias b is not used).  Dense
@@ -234,8 +218,7 @@ svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T
  * formed inside the step's first kernel, which saves the glue's own launch between stacked layers.
  * x_prev [B][d] in `wdtype`, y_prev [B][d] fp32, shift [d] fp32 (shared by the tokens): device, read;
  * x_out [B][d] in `wdtype`: device, receives x (must not alias x_prev or y_prev; the row kernel reads it).
- * The other arguments as in svdp_ffn_step; y may alias y_prev.  Always the kernel sequence
- * (SVDP_STEP_PERSISTENT does not apply).                                                          */
+ * The other arguments as in svdp_ffn_step; y may alias y_prev.                                     */
 svdp_status svdp_ffn_step_glued(const svdp_layer *layer, const void *x_prev, const float *y_prev,
                                 const float *shift, float eps, void *x_out, int32_t B, float *y,
                                 uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out,

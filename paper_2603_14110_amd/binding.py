@@ -7,7 +7,6 @@ or eager fallback: if the library has not been built, ``lib()`` raises.
 from __future__ import annotations
 
 import ctypes
-import math
 import os
 from typing import Optional, Tuple
 
@@ -18,13 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsvdp.so")
 
 SVDP_F32, SVDP_BF16 = 0, 1
-FLAG_DRELU, FLAG_REVALIDATE = 1, 2
+FLAG_DRELU, FLAG_REVALIDATE, FLAG_ENGINE_VECTOR, FLAG_ENGINE_MATRIX = 1, 2, 4, 8
 MAX_BATCH = 8
 
 EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
-    "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version", "svdp_set_step_mode",
-    "svdp_step_timeouts", "svdp_active_rows", "svdp_set_engine", "svdp_calib_workspace_bytes", "svdp_calib_bias",
+    "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version",
+    "svdp_active_rows", "svdp_calib_workspace_bytes", "svdp_calib_need", "svdp_calib_bias",
     "svdp_calib_stats_workspace_bytes", "svdp_calib_stats", "svdp_ffn_step_glued",
 ]
 
@@ -58,7 +57,7 @@ def lib() -> ctypes.CDLL:
     L.svdp_workspace_bytes.argtypes = [lp, i32]
     L.svdp_workspace_bytes.restype = sz
     L.svdp_predict.argtypes = [lp, vp, i32, vp, vp, sz, vp]
-    L.svdp_compact.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    L.svdp_compact.argtypes = [vp, i32, i32, vp, vp, vp, vp, sz, vp]
     L.svdp_sparse_ffn.argtypes = [lp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.svdp_dense_ffn.argtypes = [lp, vp, i32, vp, vp, sz, vp]
     L.svdp_ffn_step.argtypes = [lp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -72,10 +71,10 @@ def lib() -> ctypes.CDLL:
     L.svdp_status_string.restype = ctypes.c_char_p
     L.svdp_version.argtypes = []
     L.svdp_version.restype = ctypes.c_char_p
-    L.svdp_set_step_mode.argtypes = [i32, i32]
-    L.svdp_set_step_mode.restype = None
     L.svdp_calib_workspace_bytes.argtypes = [i32, i32, i32]
     L.svdp_calib_workspace_bytes.restype = ctypes.c_size_t
+    L.svdp_calib_need.argtypes = [ctypes.c_double, i32, i32]
+    L.svdp_calib_need.restype = ctypes.c_int64
     L.svdp_calib_bias.argtypes = [vp, vp, i32, i32, i32, ctypes.c_int64, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.svdp_calib_bias.restype = ctypes.c_int
     L.svdp_calib_stats_workspace_bytes.argtypes = [lp, i32]
@@ -84,10 +83,6 @@ def lib() -> ctypes.CDLL:
     L.svdp_calib_stats.restype = ctypes.c_int
     L.svdp_ffn_step_glued.argtypes = [lp, vp, vp, vp, ctypes.c_float, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     L.svdp_ffn_step_glued.restype = ctypes.c_int
-    L.svdp_set_engine.argtypes = [i32]
-    L.svdp_set_engine.restype = None
-    L.svdp_step_timeouts.argtypes = [ctypes.POINTER(ctypes.c_int32)]
-    L.svdp_step_timeouts.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -153,6 +148,7 @@ class DeviceLayer:
         return DeviceLayer(t["P"], t["Q"], t["b"], t["W_gate"], t["W_up"], t["W_downT"], self.c.flags)
 
     def with_flags(self, flags: int) -> "DeviceLayer":
+        """The same tensors under other SVDP_FLAG_* bits (pipeline variant, engine selection)."""
         t = self.tensors
         return DeviceLayer(t["P"], t["Q"], t["b"], t["W_gate"], t["W_up"], t["W_downT"], flags)
 
@@ -196,7 +192,7 @@ def compact(s: torch.Tensor):
     mask = torch.empty(max(D // 64, 1), dtype=torch.int64, device=s.device)
     idx = torch.full((D,), -1, dtype=torch.int32, device=s.device)
     nnz = torch.empty(1, dtype=torch.int32, device=s.device)
-    _check(lib().svdp_compact(_ptr(s), B, D, _ptr(mask), _ptr(idx), _ptr(nnz), _stream()), "svdp_compact")
+    _check(lib().svdp_compact(_ptr(s), B, D, _ptr(mask), _ptr(idx), _ptr(nnz), None, 0, _stream()), "svdp_compact")
     return mask, idx, nnz
 
 
@@ -265,20 +261,6 @@ def stack_glue(x: torch.Tensor, y: torch.Tensor, shift: torch.Tensor, eps: float
     return out
 
 
-STEP_SEQUENCE, STEP_PERSISTENT, STEP_MERGED_REDUCE = 0, 1, 2
-
-
-def set_step_mode(mode: int, spin_limit: int = 0) -> None:
-    lib().svdp_set_step_mode(int(mode), int(spin_limit))
-
-
-ENGINE_AUTO, ENGINE_VECTOR, ENGINE_MATRIX = 0, 1, 2
-
-
-def set_engine(engine: int) -> None:
-    lib().svdp_set_engine(int(engine))
-
-
 def calib_stats(layer: "DeviceLayer", X: torch.Tensor):
     """Damage weights and proxy scores of T calibration tokens X [T][d]: two device tensors [D][T] fp32."""
     assert X.dim() == 2 and X.is_cuda and X.is_contiguous()
@@ -296,8 +278,11 @@ def calib_stats(layer: "DeviceLayer", X: torch.Tensor):
 
 
 def calib_need(sparsity: float, D: int, T: int) -> int:
-    """Number of (neuron, sample) pairs Alg. 2's loop has to reach for a sparsity level."""
-    return min(max(int(math.ceil(sparsity * D * T)), 0), D * T)
+    """Number of (neuron, sample) pairs Alg. 2's loop has to reach for a sparsity level (computed by the library)."""
+    n = int(lib().svdp_calib_need(float(sparsity), int(D), int(T)))
+    if n < 0:
+        raise SvdpError(f"svdp_calib_need: invalid arguments sparsity={sparsity} D={D} T={T}")
+    return n
 
 
 def calib_bias(w: torch.Tensor, s: torch.Tensor, eta: int, need: int, want_kendall: bool = False):
@@ -316,12 +301,6 @@ def calib_bias(w: torch.Tensor, s: torch.Tensor, eta: int, need: int, want_kenda
     _check(lib().svdp_calib_bias(_ptr(w), _ptr(s), D, T, int(eta), int(need), _ptr(b), _ptr(k), _ptr(steps),
                                  _ptr(kend), _ptr(ws), ws.numel(), _stream()), "svdp_calib_bias")
     return b, k, steps, kend
-
-
-def step_timeouts() -> int:
-    n = ctypes.c_int32(0)
-    _check(lib().svdp_step_timeouts(ctypes.byref(n)), "svdp_step_timeouts")
-    return int(n.value)
 
 
 def version() -> str:

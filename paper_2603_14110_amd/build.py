@@ -1,14 +1,15 @@
 """Build libsvdp.so (HIP, gfx950 only) in-tree with hipcc."""
 from __future__ import annotations
 
+import glob
 import os
 import shutil
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "svdp.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "svdp_kernels.h"), os.path.join(HERE, "csrc", "svdp_device.h"),
-        os.path.join(os.path.dirname(HERE), "include", "svdp.h")]
+# every file the translation unit includes: the library is rebuilt when any of them is newer
+DEPS = [SRC, os.path.join(os.path.dirname(HERE), "include", "svdp.h")] + sorted(glob.glob(os.path.join(HERE, "csrc", "*.h")))
 LIB = os.path.join(HERE, "libsvdp.so")
 
 

@@ -1,34 +1,42 @@
 // C-ABI entry points of libsvdp (see include/svdp.h): host-side validation,
-// workspace carving and kernel launches.  No allocation, no synchronisation.
+// workspace carving and kernel launches.  No allocation, no synchronisation,
+// no state kept between calls (everything follows from a call's arguments).
 #include "../../include/svdp.h"
 
 #include <hip/hip_runtime.h>
 
 #include "svdp_kernels.h"
-#include "svdp_fused.h"
 #include "svdp_rows_mfma.h"
 #include "svdp_rows_seq.h"
 #include "svdp_calib.h"
 #include "svdp_calib_stats.h"
 
 #include <atomic>
+#include <cmath>
 #include <mutex>
 #include <type_traits>
-#include <vector>
 
 namespace {
 
 using namespace svdp;
 
 constexpr int XP_MAX_BLOCKS = 128;    // stage-1 row slabs of P (d <= 16384)
-constexpr int ROWS_BLOCKS = 256;      // k_rows blocks: one chunk of the row list and one partial y each (128 to
+constexpr int ROWS_BLOCKS = 256;      // row-kernel blocks: one chunk of the row list and one partial y each (128 to
                                       // 512 were measured; 256 is best for every batch size)
 constexpr size_t ALIGN = 256;
+constexpr size_t LDS_DEFAULT = 64 * 1024;     // dynamic LDS a kernel may use without asking
+constexpr size_t LDS_MAX = 160 * 1024;        // LDS of one gfx950 compute unit
+constexpr int MAX_DEVICES = 64;
 
 inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 inline int nb_of(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : 8; }
 inline int vec_of(int dt) { return dt == SVDP_F32 ? 4 : 8; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline bool bad_batch(int B) { return B < 1 || B > SVDP_MAX_BATCH; }
+
+constexpr uint32_t ALL_FLAGS =
+    SVDP_FLAG_DRELU | SVDP_FLAG_REVALIDATE | SVDP_FLAG_ENGINE_VECTOR | SVDP_FLAG_ENGINE_MATRIX;
 
 svdp_status check_shape(int d, int D, int r, int dt)
 {
@@ -51,7 +59,8 @@ svdp_status check_layer(const svdp_layer *L, bool need_pred, bool need_ffn)
     if (need_ffn && (!L->W_gate || !L->W_up || !L->W_downT || !aligned16(L->W_gate) ||
                      !aligned16(L->W_up) || !aligned16(L->W_downT)))
         return SVDP_ERR_INVALID_ARG;
-    if (L->flags & ~(uint32_t)(SVDP_FLAG_DRELU | SVDP_FLAG_REVALIDATE)) return SVDP_ERR_INVALID_ARG;
+    if (L->flags & ~ALL_FLAGS) return SVDP_ERR_INVALID_ARG;
+    if ((L->flags & SVDP_FLAG_ENGINE_VECTOR) && (L->flags & SVDP_FLAG_ENGINE_MATRIX)) return SVDP_ERR_INVALID_ARG;
     return SVDP_OK;
 }
 
@@ -82,26 +91,6 @@ Workspace carve(void *base, int d, int D, int r, int NB)
     return w;
 }
 
-svdp_status check_ws(const svdp_layer *L, int B, void *ws, size_t ws_bytes, Workspace *out)
-{
-    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1))) return SVDP_ERR_WORKSPACE;
-    *out = carve(ws, L->d, L->D, L->r, nb_of(B));
-    if (ws_bytes < out->bytes) return SVDP_ERR_WORKSPACE;
-    return SVDP_OK;
-}
-
-// Dynamic LDS above the default limit has to be enabled per kernel once.
-template <typename K>
-hipError_t allow_lds(K kernel, size_t bytes, int *granted)
-{
-    if ((int)bytes <= *granted) return hipSuccess;
-    if (bytes > 160 * 1024) return hipErrorInvalidValue;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e == hipSuccess) *granted = (int)bytes;
-    return e;
-}
-
 inline svdp_status hip_status(hipError_t e)
 {
     if (e == hipSuccess) e = hipGetLastError();
@@ -109,51 +98,152 @@ inline svdp_status hip_status(hipError_t e)
     return e == hipSuccess ? SVDP_OK : SVDP_ERR_HIP;
 }
 
-// ---- control blocks for launches whose blocks hand results to each other ----
-// Control blocks live in static device memory (zero at load, zero again after every
-// launch); one slot per workspace address seen by this process.
-__device__ __align__(256) uint32_t g_step_ctrl[CTRL_SLOTS * CTRL_WORDS];
-
-std::atomic<int> g_fused_mode{0};            // svdp_step_mode
-std::atomic<int> g_spin_limit{400000};       // polls before a stage wait gives up
-std::atomic<int> g_engine{0};           // svdp_engine
-std::mutex g_slot_mutex;
-std::vector<const void *> g_slots;
-uint32_t *g_ctrl_base = nullptr;
-int g_num_cus = 0;
-
-bool fused_setup()
+// Dynamic LDS above the default limit has to be enabled per kernel and device once.  What was
+// enabled is remembered per kernel (the template parameter is the kernel itself) and device;
+// the driver call is made under a lock, so that the remembered size never runs ahead of it.
+std::mutex g_grant_mutex;
+template <auto Kernel>
+bool grant_lds(size_t bytes)
 {
-    if (g_ctrl_base != nullptr) return true;
-    void *p = nullptr;
-    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_step_ctrl)) != hipSuccess || p == nullptr) {
+    static std::atomic<int> granted[MAX_DEVICES];
+    if (bytes <= LDS_DEFAULT) return true;
+    if (bytes > LDS_MAX) return false;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
         (void)hipGetLastError();
         return false;
     }
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+    if ((int)bytes <= granted[dev].load(std::memory_order_acquire)) return true;
+    std::lock_guard<std::mutex> lock(g_grant_mutex);
+    if ((int)bytes <= granted[dev].load(std::memory_order_relaxed)) return true;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)bytes) != hipSuccess) {
         (void)hipGetLastError();
         return false;
     }
-    g_num_cus = cus;
-    g_ctrl_base = static_cast<uint32_t *>(p);
+    granted[dev].store((int)bytes, std::memory_order_release);
     return true;
 }
 
-// control block of a workspace, or nullptr when none is free
-uint32_t *ctrl_for(const void *ws)
+// ---- which kernels a call uses and how much LDS they need: pure host arithmetic ----
+
+enum Engine { ENGINE_AUTO = 0, ENGINE_VECTOR = 1, ENGINE_MATRIX = 2 };
+inline Engine engine_of(const svdp_layer *L)
 {
-    std::lock_guard<std::mutex> lock(g_slot_mutex);
-    if (!fused_setup()) return nullptr;
-    for (size_t i = 0; i < g_slots.size(); ++i)
-        if (g_slots[i] == ws) return g_ctrl_base + i * CTRL_WORDS;
-    if (g_slots.size() >= (size_t)CTRL_SLOTS) return nullptr;
-    g_slots.push_back(ws);
-    return g_ctrl_base + (g_slots.size() - 1) * CTRL_WORDS;
+    return (L->flags & SVDP_FLAG_ENGINE_VECTOR) ? ENGINE_VECTOR
+                                                : (L->flags & SVDP_FLAG_ENGINE_MATRIX) ? ENGINE_MATRIX : ENGINE_AUTO;
 }
 
-// ---- launch helpers, one per kernel, templated on storage type and batch capacity ----
+template <typename W, int NB>
+size_t xp_lds(const svdp_layer *)
+{
+    constexpr int VEC = Elem<W>::VEC;
+    const size_t outs = (size_t)NB * XP_COLS;
+    const size_t parts = XP_THREADS / outs >= 1 ? XP_THREADS / outs : 1;
+    const size_t nsub = XP_THREADS / (XP_COLS / VEC);
+    return ((size_t)NB * XP_ROWS + nsub * (outs + 1) + parts * outs) * 4;
+}
+
+// Whether the score kernel on the matrix cores takes this layer and batch capacity.
+template <typename W, int NB>
+bool scores_on_matrix(const svdp_layer *L)
+{
+    if (!std::is_same<W, bf16>::value) return false;
+    const Engine engine = engine_of(L);
+    const bool want = engine == ENGINE_MATRIX || (engine == ENGINE_AUTO && NB >= 4);
+    return want && L->r % 32 == 0 && L->r <= 32 * SCM_KB;
+}
+template <int NB>
+constexpr int scores_threads() { return NB <= 2 ? 512 : 256; }
+template <typename W, int NB>
+size_t scores_lds(const svdp_layer *L)
+{
+    if (scores_on_matrix<W, NB>(L)) return (size_t)3 * NB * L->r * 2;
+    const size_t thr = scores_threads<NB>();
+    const size_t tsp = (size_t)NB * L->r > thr * 4 ? (size_t)NB * L->r : thr * 4;
+    return ((size_t)NB * L->r + (size_t)NB * SC_SLAB + tsp) * 4;
+}
+
+enum RowsKind { ROWS_VECTOR = 0, ROWS_SEQ = 1, ROWS_MATRIX = 2 };
+struct RowsPlan {
+    RowsKind kind;
+    int max_chunk;      // LDS row capacity of a block
+    int min_chunk;      // fewest rows a block takes (short lists use fewer blocks)
+    size_t lds;
+};
+
+template <typename W, int NB>
+RowsPlan plan_rows(const svdp_layer *L)
+{
+    const int d = L->d, D = L->D, G = ROWS_BLOCKS;
+    const int per = (D + G - 1) / G;
+    RowsPlan p;
+    if ((L->flags & SVDP_FLAG_REVALIDATE) != 0) {
+        p.kind = ROWS_SEQ;
+        p.min_chunk = 4;
+        p.max_chunk = round_up(per > p.min_chunk ? per : p.min_chunk, ROWS_UB);
+        p.lds = (size_t)NB * d * sizeof(W) + ((size_t)2 * NB * p.max_chunk + (size_t)3 * p.max_chunk) * 4;
+        return p;
+    }
+    if (std::is_same<W, bf16>::value) {
+        const Engine engine = engine_of(L);
+        // measured on the Mistral shape: ahead of the vector kernel only at the largest batch capacity
+        const bool want = engine == ENGINE_MATRIX || (engine == ENGINE_AUTO && NB >= 8);
+        if (want && d % 512 == 0) {
+            p.kind = ROWS_MATRIX;
+            p.min_chunk = MF_ROWS;
+            p.max_chunk = round_up(per > p.min_chunk ? per : p.min_chunk, MF_ROWS);
+            p.lds = (size_t)NB * d * 2 +
+                    ((size_t)ROWS_WAVES * p.max_chunk * 2 * NB + (size_t)p.max_chunk * MF_TOK + p.max_chunk) * 4;
+            if (p.lds <= LDS_MAX) return p;
+        }
+    }
+    p.kind = ROWS_VECTOR;
+    p.min_chunk = 4;
+    p.max_chunk = round_up(per > p.min_chunk ? per : p.min_chunk, ROWS_UB);
+    p.lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * p.max_chunk + p.max_chunk) * 4;
+    return p;
+}
+
+// dispatch on (dtype, batch capacity): f(W tag, NB constant)
+template <typename T>
+struct Tag {
+    using type = T;
+};
+template <typename F>
+auto dispatch(int dt, int NBv, F &&f)
+{
+    auto on_nb = [&](auto wtag) {
+        switch (NBv) {
+        case 1: return f(wtag, std::integral_constant<int, 1>{});
+        case 2: return f(wtag, std::integral_constant<int, 2>{});
+        case 4: return f(wtag, std::integral_constant<int, 4>{});
+        default: return f(wtag, std::integral_constant<int, 8>{});
+        }
+    };
+    return dt == SVDP_F32 ? on_nb(Tag<float>{}) : on_nb(Tag<bf16>{});
+}
+
+// Everything every kernel of the layer needs fits the LDS of a compute unit (pure).
+bool layer_fits(const svdp_layer *L, int NBv)
+{
+    return dispatch(L->wdtype, NBv, [&](auto wt, auto nb) {
+        using W = typename decltype(wt)::type;
+        constexpr int NB = decltype(nb)::value;
+        return xp_lds<W, NB>(L) <= LDS_MAX && scores_lds<W, NB>(L) <= LDS_MAX && plan_rows<W, NB>(L).lds <= LDS_MAX;
+    });
+}
+
+svdp_status check_ws(const svdp_layer *L, int B, void *ws, size_t ws_bytes, Workspace *out)
+{
+    if (!layer_fits(L, nb_of(B))) return SVDP_ERR_UNSUPPORTED;
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1))) return SVDP_ERR_WORKSPACE;
+    *out = carve(ws, L->d, L->D, L->r, nb_of(B));
+    if (ws_bytes < out->bytes) return SVDP_ERR_WORKSPACE;
+    return SVDP_OK;
+}
+
+// ---- preparation (LDS grants; nothing is enqueued) and launch, per kernel ----
 
 // The stacked benchmark's glue folded into the first kernel of a step (svdp_ffn_step_glued).
 struct GlueArgs {
@@ -164,25 +254,25 @@ struct GlueArgs {
 };
 
 template <typename W, int NB>
-svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, int *nt_out, hipStream_t st,
-                      const GlueArgs *glue = nullptr)
+bool prepare_xP(const svdp_layer *L, bool glue)
 {
-    constexpr int VEC = Elem<W>::VEC;
+    const size_t lds = xp_lds<W, NB>(L);
+    return glue ? grant_lds<k_xP<W, NB, true>>(lds) : grant_lds<k_xP<W, NB, false>>(lds);
+}
+
+template <typename W, int NB>
+svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, int *nt_out, hipStream_t st,
+                      const GlueArgs *glue)
+{
     const int d = L->d, r = L->r;
     const int nt = (d + XP_ROWS - 1) / XP_ROWS;           // <= XP_MAX_BLOCKS since d <= 16384
     const int ncs = (r + XP_COLS - 1) / XP_COLS;
-    const size_t outs = (size_t)NB * XP_COLS;
-    const size_t parts = XP_THREADS / outs >= 1 ? XP_THREADS / outs : 1;
-    const size_t nsub = XP_THREADS / (XP_COLS / VEC);
-    const size_t lds = ((size_t)NB * XP_ROWS + nsub * (outs + 1) + parts * outs) * 4;
-    static int granted = 64 * 1024, granted_g = 64 * 1024;
+    const size_t lds = xp_lds<W, NB>(L);
     if (glue != nullptr) {
-        if (allow_lds(k_xP<W, NB, true>, lds, &granted_g) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
         hipLaunchKernelGGL((k_xP<W, NB, true>), dim3(nt, ncs), dim3(XP_THREADS), lds, st, static_cast<const W *>(L->P),
                            static_cast<const W *>(x), B, d, r, tpart, glue->y_prev, glue->shift, glue->eps,
                            static_cast<W *>(glue->x_out));
     } else {
-        if (allow_lds(k_xP<W, NB, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
         hipLaunchKernelGGL((k_xP<W, NB, false>), dim3(nt, ncs), dim3(XP_THREADS), lds, st,
                            static_cast<const W *>(L->P), static_cast<const W *>(x), B, d, r, tpart, nullptr, nullptr,
                            0.f, nullptr);
@@ -191,253 +281,129 @@ svdp_status launch_xP(const svdp_layer *L, const void *x, int B, float *tpart, i
     return hip_status(hipSuccess);
 }
 
-template <typename W, int NB, int LPR_LOG2, int THREADS>
-svdp_status launch_scores_thr(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
-                              uint64_t *mask_out, hipStream_t st)
+// lanes per row of the vector score kernel: 2^k >= 16-byte column groups per row of Q, 8..64
+template <typename W>
+int scores_lpr_log2(const svdp_layer *L)
 {
-    const size_t tsp = (size_t)NB * L->r > (size_t)THREADS * 4 ? (size_t)NB * L->r : (size_t)THREADS * 4;
-    const size_t lds = ((size_t)NB * L->r + (size_t)NB * SC_SLAB + tsp) * 4;
-    static int granted = 64 * 1024;
-    if (allow_lds(k_scores<W, NB, LPR_LOG2, THREADS>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_scores<W, NB, LPR_LOG2, THREADS>), dim3(L->D / SC_SLAB), dim3(THREADS), lds, st,
-                       static_cast<const W *>(L->Q), L->b, tpart, nt, B, L->D, L->r, s_out, mask_out);
-    return hip_status(hipSuccess);
+    const int cg = L->r / Elem<W>::VEC;
+    return cg <= 8 ? 3 : cg <= 16 ? 4 : cg <= 32 ? 5 : 6;
 }
 
-template <typename W, int NB, int LPR_LOG2>
-svdp_status launch_scores_lpr(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
-                              uint64_t *mask_out, hipStream_t st)
+template <typename W, int NB, typename F>
+auto with_scores_kernel(const svdp_layer *L, F &&f)
 {
-    // block size: 512 threads for one or two tokens (short critical path), 256 for larger batches
-    // (fewer wavefronts repeating the per-wave overhead); measured on the 7B and Mistral shapes
-    if (NB <= 2) return launch_scores_thr<W, NB, LPR_LOG2, 512>(L, tpart, nt, B, s_out, mask_out, st);
-    return launch_scores_thr<W, NB, LPR_LOG2, 256>(L, tpart, nt, B, s_out, mask_out, st);
-}
-
-// Whether the score kernel on the matrix cores takes this layer and batch capacity.
-template <typename W, int NB>
-bool scores_on_matrix(const svdp_layer *L)
-{
-    if (!std::is_same<W, bf16>::value) return false;
-    const int engine = g_engine.load();
-    const bool want = engine == SVDP_ENGINE_MATRIX || (engine == SVDP_ENGINE_AUTO && NB >= 4);
-    return want && L->r % 32 == 0 && L->r <= 32 * SCM_KB;
+    constexpr int THR = scores_threads<NB>();
+    switch (scores_lpr_log2<W>(L)) {
+    case 3: return f(std::integral_constant<decltype(&k_scores<W, NB, 3, THR>), &k_scores<W, NB, 3, THR>>{});
+    case 4: return f(std::integral_constant<decltype(&k_scores<W, NB, 4, THR>), &k_scores<W, NB, 4, THR>>{});
+    case 5: return f(std::integral_constant<decltype(&k_scores<W, NB, 5, THR>), &k_scores<W, NB, 5, THR>>{});
+    default: return f(std::integral_constant<decltype(&k_scores<W, NB, 6, THR>), &k_scores<W, NB, 6, THR>>{});
+    }
 }
 
 template <typename W, int NB>
-svdp_status launch_scores(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out,
-                          uint64_t *mask_out, hipStream_t st)
+bool prepare_scores(const svdp_layer *L)
 {
+    const size_t lds = scores_lds<W, NB>(L);
+    if constexpr (std::is_same<W, bf16>::value) {
+        if (scores_on_matrix<W, NB>(L)) return grant_lds<k_scores_mfma<NB>>(lds);
+    }
+    return with_scores_kernel<W, NB>(L, [&](auto k) { return grant_lds<decltype(k)::value>(lds); });
+}
+
+template <typename W, int NB>
+svdp_status launch_scores(const svdp_layer *L, const float *tpart, int nt, int B, float *s_out, uint64_t *mask_out,
+                          hipStream_t st)
+{
+    const size_t lds = scores_lds<W, NB>(L);
     if constexpr (std::is_same<W, bf16>::value) {
         if (scores_on_matrix<W, NB>(L)) {
-            const size_t lds = (size_t)3 * NB * L->r * 2;
             hipLaunchKernelGGL((k_scores_mfma<NB>), dim3(L->D / SC_SLAB), dim3(SCM_THREADS), lds, st,
                                static_cast<const bf16 *>(L->Q), L->b, tpart, nt, B, L->D, L->r, s_out, mask_out);
             return hip_status(hipSuccess);
         }
     }
-    const int cg = L->r / Elem<W>::VEC;       // 16-byte column groups per row of Q
-    if (cg <= 8) return launch_scores_lpr<W, NB, 3>(L, tpart, nt, B, s_out, mask_out, st);
-    if (cg <= 16) return launch_scores_lpr<W, NB, 4>(L, tpart, nt, B, s_out, mask_out, st);
-    if (cg <= 32) return launch_scores_lpr<W, NB, 5>(L, tpart, nt, B, s_out, mask_out, st);
-    return launch_scores_lpr<W, NB, 6>(L, tpart, nt, B, s_out, mask_out, st);
+    // block size: 512 threads for one or two tokens (short critical path), 256 for larger batches
+    // (fewer wavefronts repeating the per-wave overhead); measured on the 7B and Mistral shapes
+    with_scores_kernel<W, NB>(L, [&](auto k) {
+        hipLaunchKernelGGL(decltype(k)::value, dim3(L->D / SC_SLAB), dim3(scores_threads<NB>()), lds, st,
+                           static_cast<const W *>(L->Q), L->b, tpart, nt, B, L->D, L->r, s_out, mask_out);
+        return 0;
+    });
+    return hip_status(hipSuccess);
 }
 
-// The row kernel on the matrix cores, if this layer and batch qualify: launches it and
-// returns true (status in *out); false when the vector kernel has to do the work.
 template <typename W, int NB, int MODE>
-bool launch_rows_matrix(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
-                        const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, hipStream_t st,
-                        svdp_status *out)
+bool prepare_rows(const svdp_layer *L)
 {
-    if constexpr (!std::is_same<W, bf16>::value) {
-        return false;
-    } else {
-        const int engine = g_engine.load();
-        // measured on the Mistral shape: ahead of the vector kernel only at the largest batch capacity
-        if (engine == SVDP_ENGINE_VECTOR || (engine == SVDP_ENGINE_AUTO && NB < 8)) return false;
-        if (L->d % 512 != 0 || (L->flags & SVDP_FLAG_REVALIDATE) != 0) return false;
-        const int d = L->d, D = L->D, grid = ROWS_BLOCKS;
-        const int max_chunk = ((D + grid - 1) / grid + MF_ROWS - 1) / MF_ROWS * MF_ROWS;
-        const size_t lds = (size_t)NB * d * 2 +
-                           ((size_t)ROWS_WAVES * max_chunk * 2 * NB + (size_t)max_chunk * MF_TOK + max_chunk) * 4;
-        static int granted = 64 * 1024;
-        if (lds > 160 * 1024 || allow_lds(k_rows_mfma<NB, MODE>, lds, &granted) != hipSuccess) return false;
-        hipLaunchKernelGGL((k_rows_mfma<NB, MODE>), dim3(grid), dim3(ROWS_THREADS), lds, st,
-                           static_cast<const bf16 *>(L->W_gate), static_cast<const bf16 *>(L->W_up),
-                           static_cast<const bf16 *>(L->W_downT), static_cast<const bf16 *>(x), B, d, D, mask, idx_in,
-                           nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart);
-        *out = hip_status(hipSuccess);
-        return true;
+    const RowsPlan p = plan_rows<W, NB>(L);
+    if (p.kind == ROWS_SEQ) return grant_lds<k_rows_seq<W, NB, MODE>>(p.lds);
+    if constexpr (std::is_same<W, bf16>::value) {
+        if (p.kind == ROWS_MATRIX) return grant_lds<k_rows_mfma<NB, MODE>>(p.lds);
     }
+    return grant_lds<k_rows<W, NB, MODE>>(p.lds);
 }
 
-// The row kernel of the sequential pipeline (SVDP_FLAG_REVALIDATE), launched in place of k_rows.
+// The row kernel (gate, up, partial down projection per block) without the sum of the partials.
 template <typename W, int NB, int MODE>
-svdp_status launch_rows_seq(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
-                            const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w,
-                            hipStream_t st)
+svdp_status launch_rows_only(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
+                             const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w,
+                             hipStream_t st)
 {
-    const int d = L->d, D = L->D, grid = ROWS_BLOCKS;
-    const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
-    const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)2 * NB * max_chunk + (size_t)3 * max_chunk) * 4;
-    static int granted = 64 * 1024;
-    if (allow_lds(k_rows_seq<W, NB, MODE>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_rows_seq<W, NB, MODE>), dim3(grid), dim3(ROWS_THREADS), lds, st,
-                       static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
-                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, mask, idx_in, nnz_in,
-                       idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart);
+    const RowsPlan p = plan_rows<W, NB>(L);
+    const int d = L->d, D = L->D;
+    const W *Wg = static_cast<const W *>(L->W_gate), *Wu = static_cast<const W *>(L->W_up);
+    const W *Wd = static_cast<const W *>(L->W_downT), *xs = static_cast<const W *>(x);
+    if (p.kind == ROWS_SEQ) {
+        hipLaunchKernelGGL((k_rows_seq<W, NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs, B,
+                           d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags,
+                           w.ypart);
+        return hip_status(hipSuccess);
+    }
+    if constexpr (std::is_same<W, bf16>::value) {
+        if (p.kind == ROWS_MATRIX) {
+            hipLaunchKernelGGL((k_rows_mfma<NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs,
+                               B, d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk,
+                               L->flags, w.ypart);
+            return hip_status(hipSuccess);
+        }
+    }
+    hipLaunchKernelGGL((k_rows<W, NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs, B, d, D,
+                       mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags, w.ypart);
     return hip_status(hipSuccess);
 }
 
 template <typename W, int NB, int MODE>
 svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
-                        const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base,
-                        float *y, hipStream_t st)
+                        const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, float *y,
+                        hipStream_t st)
 {
-    const int d = L->d, D = L->D;
-    const int grid = ROWS_BLOCKS;
-    const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
-    size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
-    const size_t lds_tail = (size_t)ROWS_THREADS * 16;          // the in-launch reduction's tree
-    const W *Wg = static_cast<const W *>(L->W_gate), *Wu = static_cast<const W *>(L->W_up);
-    const W *Wd = static_cast<const W *>(L->W_downT), *xs = static_cast<const W *>(x);
-
-    // Variant that also finishes y inside the launch (needs every block resident at once).
-    if (g_fused_mode.load() == SVDP_STEP_MERGED_REDUCE) {
-        uint32_t *ctrl = ctrl_for(ws_base);
-        const size_t lds_f = lds > lds_tail ? lds : lds_tail;
-        static int granted_f = 64 * 1024;
-        static int resident = -1;
-        if (ctrl != nullptr && allow_lds(k_rows<W, NB, MODE, true>, lds_f, &granted_f) == hipSuccess) {
-            if (resident < 0) {
-                int nb = 0;
-                if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_rows<W, NB, MODE, true>, ROWS_THREADS,
-                                                                 160 * 1024 / 2) != hipSuccess) {
-                    (void)hipGetLastError();
-                    nb = 0;
-                }
-                resident = nb;      // with half the LDS of a CU per block: a lower bound for smaller requests
-            }
-            const bool fits = lds_f <= 160 * 1024 / 2 ? resident * g_num_cus >= grid : g_num_cus >= grid;
-            if (fits && lds_f <= 160 * 1024) {
-                hipLaunchKernelGGL((k_rows<W, NB, MODE, true>), dim3(grid), dim3(ROWS_THREADS), lds_f, st, Wg, Wu, Wd,
-                                   xs, B, d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags,
-                                   w.ypart, y, ctrl, g_spin_limit.load());
-                return hip_status(hipSuccess);
-            }
-        }
-    }
-    svdp_status s;
-    if ((L->flags & SVDP_FLAG_REVALIDATE) != 0) {
-        s = launch_rows_seq<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st);
-    } else if (!launch_rows_matrix<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st, &s)) {
-        static int granted = 64 * 1024;
-        if (allow_lds(k_rows<W, NB, MODE, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL((k_rows<W, NB, MODE, false>), dim3(grid), dim3(ROWS_THREADS), lds, st, Wg, Wu, Wd, xs, B, d,
-                           D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, max_chunk, L->flags, w.ypart, y, nullptr,
-                           0);
-        s = hip_status(hipSuccess);
-    }
+    const svdp_status s = launch_rows_only<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st);
     if (s != SVDP_OK) return s;
-    const int vpt = d / 4;
+    const RowsPlan p = plan_rows<W, NB>(L);
+    const int vpt = L->d / 4;
     const int blocks = B * ((vpt + RED_COLS - 1) / RED_COLS);
     hipLaunchKernelGGL(k_reduce_y, dim3(blocks), dim3(RED_COLS * RED_SEGS), 0, st, w.ypart,
-                       MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, grid, NB, B, d, y);
+                       MODE == ROWS_DENSE ? nullptr : w.nnz, L->D, L->D, ROWS_BLOCKS, p.min_chunk, NB, B, L->d, y);
     return hip_status(hipSuccess);
 }
-
-svdp_status launch_compact(const uint64_t *mask, int D, int32_t *idx, int32_t *nnz, hipStream_t st)
-{
-    hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(SCAN_THREADS), 0, st, mask, D / 64, idx, nnz);
-    return hip_status(hipSuccess);
-}
-
-inline int fused_max_chunk(int D, int G) { return ((D + G - 1) / G + ROWS_UB - 1) / ROWS_UB * ROWS_UB; }
 
 template <typename W, int NB>
-size_t fused_lds_bytes(const svdp_layer *L, int G)
+bool tsum_needed(const svdp_layer *L)
 {
-    constexpr int VEC = Elem<W>::VEC;
-    const size_t s1 = (size_t)(256 / (XP_COLS / VEC)) * NB * XP_COLS * 4;
-    const size_t tsp = (size_t)NB * L->r > (size_t)FUSED_THREADS * 4 ? (size_t)NB * L->r : (size_t)FUSED_THREADS * 4;
-    const size_t s2 = ((size_t)NB * L->r + (size_t)NB * SC_SLAB + tsp) * 4;
-    const int mc = fused_max_chunk(L->D, G);
-    const size_t s3 = ((size_t)L->D / 64 + 2) * 8 + ((size_t)NB * mc + mc) * 4;
-    const size_t s4 = (size_t)FUSED_THREADS * 16;
-    size_t scratch = s1 > s2 ? s1 : s2;
-    scratch = scratch > s3 ? scratch : s3;
-    scratch = scratch > s4 ? scratch : s4;
-    return (size_t)NB * L->d * sizeof(W) + scratch;
+    // finish t once instead of in every score block (the vector score kernel splits the partial
+    // list over threads through LDS, which costs more than a launch from 4 tokens up)
+    return NB >= 4 && L->d > XP_ROWS && !scores_on_matrix<W, NB>(L);
 }
-
-// SVDP_ERR_UNSUPPORTED means "use the kernel sequence instead"
-template <typename W, int NB>
-svdp_status run_step_fused(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
-                           int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st)
-{
-    constexpr int VEC = Elem<W>::VEC;
-    uint32_t *ctrl = ctrl_for(ws_base);
-    if (ctrl == nullptr) return SVDP_ERR_UNSUPPORTED;
-    const int G = g_num_cus < ROWS_BLOCKS ? g_num_cus : ROWS_BLOCKS;
-    if (L->D / 64 > 4096) return SVDP_ERR_UNSUPPORTED;
-    const size_t lds = fused_lds_bytes<W, NB>(L, G);
-    if (lds > 160 * 1024) return SVDP_ERR_UNSUPPORTED;
-    static int granted = 64 * 1024;
-    if (allow_lds(k_step_fused<W, NB>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    static int resident = -1;      // blocks of this kernel one CU can hold (1024 threads each)
-    if (resident < 0) {
-        int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_step_fused<W, NB>, FUSED_THREADS, lds) != hipSuccess) {
-            (void)hipGetLastError();
-            nb = 0;
-        }
-        resident = nb;
-    }
-    if (resident < 1) return SVDP_ERR_UNSUPPORTED;
-    const int cg = L->r / VEC;
-    int lpr_log2 = 3;
-    while ((1 << lpr_log2) < cg && lpr_log2 < 6) ++lpr_log2;
-    hipLaunchKernelGGL((k_step_fused<W, NB>), dim3(G), dim3(FUSED_THREADS), lds, st, static_cast<const W *>(L->P),
-                       static_cast<const W *>(L->Q), L->b, static_cast<const W *>(L->W_gate),
-                       static_cast<const W *>(L->W_up), static_cast<const W *>(L->W_downT), static_cast<const W *>(x),
-                       B, L->d, L->D, L->r, lpr_log2, L->flags, w.tpart, w.mask, w.ypart, fused_max_chunk(L->D, G), y,
-                       mask_out, idx_out, nnz_out, ctrl, g_spin_limit.load());
-    return hip_status(hipSuccess);
-}
-
-// dispatch on (dtype, batch capacity)
-#define SVDP_DISPATCH(dt, NBv, CALL)                                                         \
-    do {                                                                                     \
-        if ((dt) == SVDP_F32) {                                                              \
-            using W = float;                                                                 \
-            switch (NBv) {                                                                   \
-            case 1: { constexpr int NB = 1; return CALL; }                                   \
-            case 2: { constexpr int NB = 2; return CALL; }                                   \
-            case 4: { constexpr int NB = 4; return CALL; }                                   \
-            default: { constexpr int NB = 8; return CALL; }                                  \
-            }                                                                                \
-        } else {                                                                             \
-            using W = bf16;                                                                  \
-            switch (NBv) {                                                                   \
-            case 1: { constexpr int NB = 1; return CALL; }                                   \
-            case 2: { constexpr int NB = 2; return CALL; }                                   \
-            case 4: { constexpr int NB = 4; return CALL; }                                   \
-            default: { constexpr int NB = 8; return CALL; }                                  \
-            }                                                                                \
-        }                                                                                    \
-    } while (0)
 
 template <typename W, int NB>
 svdp_status run_predict(const svdp_layer *L, const void *x, int B, float *s, uint64_t *mask, const Workspace &w,
-                        hipStream_t st, const GlueArgs *glue = nullptr)
+                        hipStream_t st, const GlueArgs *glue)
 {
     int nt = 0;
     svdp_status e = launch_xP<W, NB>(L, x, B, w.tpart, &nt, st, glue);
     if (e != SVDP_OK) return e;
-    if (NB >= 4 && nt > 1 && !scores_on_matrix<W, NB>(L)) {
-        // finish t once instead of in every score block (the vector score kernel splits the
-        // partial list over threads through LDS, which costs more than a launch from 4 tokens up)
+    if (tsum_needed<W, NB>(L)) {
         const int count = NB * L->r;
         float *t = w.tpart + (size_t)XP_MAX_BLOCKS * NB * L->r;
         hipLaunchKernelGGL(k_tsum, dim3((count + 255) / 256), dim3(256), 0, st, w.tpart, nt, count, t);
@@ -448,79 +414,23 @@ svdp_status run_predict(const svdp_layer *L, const void *x, int B, float *s, uin
     return launch_scores<W, NB>(L, w.tpart, nt, B, s, mask, st);
 }
 
-template <typename W, int NB>
-svdp_status run_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
-                     int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st,
-                     const GlueArgs *glue = nullptr)
+// The whole step: every LDS grant first (on failure nothing has been enqueued), then the launches.
+svdp_status step_impl(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out, int32_t *idx_out,
+                      int32_t *nnz_out, const Workspace &w, hipStream_t st, const GlueArgs *glue)
 {
-    if (glue != nullptr) {
-        // x is made by the first kernel (from x_prev = x); the row kernel reads it from x_out
+    return dispatch(L->wdtype, nb_of(B), [&](auto wt, auto nb) -> svdp_status {
+        using W = typename decltype(wt)::type;
+        constexpr int NB = decltype(nb)::value;
+        if (!prepare_xP<W, NB>(L, glue != nullptr) || !prepare_scores<W, NB>(L) || !prepare_rows<W, NB, ROWS_MASK>(L))
+            return SVDP_ERR_UNSUPPORTED;
         uint64_t *mask = mask_out ? mask_out : w.mask;
-        svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st, glue);
+        const svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st, glue);
         if (e != SVDP_OK) return e;
-        return launch_rows<W, NB, ROWS_MASK>(L, glue->x_out, B, mask, nullptr, nullptr, idx_out, nnz_out, w, ws_base, y,
-                                             st);
-    }
-    if (g_fused_mode.load() == SVDP_STEP_PERSISTENT) {
-        const svdp_status f = run_step_fused<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st);
-        if (f != SVDP_ERR_UNSUPPORTED) return f;
-    }
-    uint64_t *mask = mask_out ? mask_out : w.mask;
-    svdp_status e = run_predict<W, NB>(L, x, B, nullptr, mask, w, st);
-    if (e != SVDP_OK) return e;
-    return launch_rows<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, idx_out, nnz_out, w, ws_base, y, st);
+        // with the glue, x is made by the first kernel (from x_prev = x) and the row kernel reads it from x_out
+        const void *xr = glue != nullptr ? glue->x_out : x;
+        return launch_rows<W, NB, ROWS_MASK>(L, xr, B, mask, nullptr, nullptr, idx_out, nnz_out, w, y, st);
+    });
 }
-
-svdp_status dispatch_predict(const svdp_layer *L, const void *x, int B, float *s, const Workspace &w, hipStream_t st)
-{
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (run_predict<W, NB>(L, x, B, s, nullptr, w, st)));
-}
-svdp_status dispatch_sparse(const svdp_layer *L, const void *x, int B, const int32_t *idx, const int32_t *nnz,
-                            float *y, const Workspace &w, void *ws_base, hipStream_t st)
-{
-    SVDP_DISPATCH(L->wdtype, nb_of(B),
-                  (launch_rows<W, NB, ROWS_LIST>(L, x, B, nullptr, idx, nnz, nullptr, nullptr, w, ws_base, y, st)));
-}
-svdp_status dispatch_dense(const svdp_layer *L, const void *x, int B, float *y, const Workspace &w, void *ws_base,
-                           hipStream_t st)
-{
-    SVDP_DISPATCH(L->wdtype, nb_of(B),
-                  (launch_rows<W, NB, ROWS_DENSE>(L, x, B, nullptr, nullptr, nullptr, nullptr, nullptr, w, ws_base, y, st)));
-}
-template <typename W, int NB>
-svdp_status launch_rows_only(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const Workspace &w,
-                             hipStream_t st)
-{
-    const int d = L->d, D = L->D;
-    const int grid = ROWS_BLOCKS;
-    const int max_chunk = ((D + grid - 1) / grid + ROWS_UB - 1) / ROWS_UB * ROWS_UB;
-    const size_t lds = (size_t)NB * d * sizeof(W) + ((size_t)NB * max_chunk + max_chunk) * 4;
-    if ((L->flags & SVDP_FLAG_REVALIDATE) != 0)
-        return launch_rows_seq<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, st);
-    svdp_status sm;
-    if (launch_rows_matrix<W, NB, ROWS_MASK>(L, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, st, &sm)) return sm;
-    static int granted = 64 * 1024;
-    if (allow_lds(k_rows<W, NB, ROWS_MASK, false>, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_rows<W, NB, ROWS_MASK, false>), dim3(grid), dim3(ROWS_THREADS), lds, st,
-                       static_cast<const W *>(L->W_gate), static_cast<const W *>(L->W_up),
-                       static_cast<const W *>(L->W_downT), static_cast<const W *>(x), B, d, D, mask, nullptr, nullptr,
-                       nullptr, nullptr, w.nnz, max_chunk, L->flags, w.ypart, nullptr, nullptr, 0);
-    return hip_status(hipSuccess);
-}
-svdp_status dispatch_rows_only(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const Workspace &w,
-                               hipStream_t st)
-{
-    SVDP_DISPATCH(L->wdtype, nb_of(B), (launch_rows_only<W, NB>(L, x, B, mask, w, st)));
-}
-svdp_status dispatch_step(const svdp_layer *L, const void *x, int B, float *y, uint64_t *mask_out,
-                          int32_t *idx_out, int32_t *nnz_out, const Workspace &w, void *ws_base, hipStream_t st,
-                          const GlueArgs *glue = nullptr)
-{
-    SVDP_DISPATCH(L->wdtype, nb_of(B),
-                  (run_step<W, NB>(L, x, B, y, mask_out, idx_out, nnz_out, w, ws_base, st, glue)));
-}
-
-inline bool bad_batch(int B) { return B < 1 || B > SVDP_MAX_BATCH; }
 
 }  // namespace
 
@@ -530,6 +440,10 @@ size_t svdp_workspace_bytes(const svdp_layer *layer, int32_t max_batch)
 {
     if (layer == nullptr || bad_batch(max_batch)) return 0;
     if (check_shape(layer->d, layer->D, layer->r, layer->wdtype) != SVDP_OK) return 0;
+    if ((layer->flags & ~ALL_FLAGS) ||
+        ((layer->flags & SVDP_FLAG_ENGINE_VECTOR) && (layer->flags & SVDP_FLAG_ENGINE_MATRIX)))
+        return 0;
+    if (!layer_fits(layer, nb_of(max_batch))) return 0;
     return carve(nullptr, layer->d, layer->D, layer->r, nb_of(max_batch)).bytes;
 }
 
@@ -542,19 +456,27 @@ svdp_status svdp_predict(const svdp_layer *layer, const void *x, int32_t B, floa
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_predict(layer, x, B, s, w, static_cast<hipStream_t>(stream));
+    return dispatch(layer->wdtype, nb_of(B), [&](auto wt, auto nb) -> svdp_status {
+        using W = typename decltype(wt)::type;
+        constexpr int NB = decltype(nb)::value;
+        if (!prepare_xP<W, NB>(layer, false) || !prepare_scores<W, NB>(layer)) return SVDP_ERR_UNSUPPORTED;
+        return run_predict<W, NB>(layer, x, B, s, nullptr, w, static_cast<hipStream_t>(stream), nullptr);
+    });
 }
 
 svdp_status svdp_compact(const float *s, int32_t B, int32_t D, uint64_t *mask, int32_t *idx, int32_t *nnz,
-                         void *stream)
+                         void *ws, size_t ws_bytes, void *stream)
 {
+    (void)ws;
+    (void)ws_bytes;
     if (s == nullptr || mask == nullptr || idx == nullptr || nnz == nullptr || bad_batch(B) || D <= 0) return SVDP_ERR_INVALID_ARG;
     if (D % 64 != 0) return SVDP_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(k_mask_from_scores, dim3((D / 64 + 3) / 4), dim3(256), 0, st, s, B, D, mask);
-    svdp_status e = hip_status(hipSuccess);
+    const svdp_status e = hip_status(hipSuccess);
     if (e != SVDP_OK) return e;
-    return launch_compact(mask, D, idx, nnz, st);
+    hipLaunchKernelGGL(k_compact_scan, dim3(1), dim3(SCAN_THREADS), 0, st, mask, D / 64, idx, nnz);
+    return hip_status(hipSuccess);
 }
 
 svdp_status svdp_sparse_ffn(const svdp_layer *layer, const void *x, int32_t B, const int32_t *idx,
@@ -568,7 +490,13 @@ svdp_status svdp_sparse_ffn(const svdp_layer *layer, const void *x, int32_t B, c
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_sparse(layer, x, B, idx, nnz, y, w, ws, static_cast<hipStream_t>(stream));
+    return dispatch(layer->wdtype, nb_of(B), [&](auto wt, auto nb) -> svdp_status {
+        using W = typename decltype(wt)::type;
+        constexpr int NB = decltype(nb)::value;
+        if (!prepare_rows<W, NB, ROWS_LIST>(layer)) return SVDP_ERR_UNSUPPORTED;
+        return launch_rows<W, NB, ROWS_LIST>(layer, x, B, nullptr, idx, nnz, nullptr, nullptr, w, y,
+                                             static_cast<hipStream_t>(stream));
+    });
 }
 
 svdp_status svdp_dense_ffn(const svdp_layer *layer, const void *x, int32_t B, float *y, void *ws, size_t ws_bytes,
@@ -580,7 +508,13 @@ svdp_status svdp_dense_ffn(const svdp_layer *layer, const void *x, int32_t B, fl
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_dense(layer, x, B, y, w, ws, static_cast<hipStream_t>(stream));
+    return dispatch(layer->wdtype, nb_of(B), [&](auto wt, auto nb) -> svdp_status {
+        using W = typename decltype(wt)::type;
+        constexpr int NB = decltype(nb)::value;
+        if (!prepare_rows<W, NB, ROWS_DENSE>(layer)) return SVDP_ERR_UNSUPPORTED;
+        return launch_rows<W, NB, ROWS_DENSE>(layer, x, B, nullptr, nullptr, nullptr, nullptr, nullptr, w, y,
+                                              static_cast<hipStream_t>(stream));
+    });
 }
 
 svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, float *y, uint64_t *mask_out,
@@ -592,7 +526,7 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_step(layer, x, B, y, mask_out, idx_out, nnz_out, w, ws, static_cast<hipStream_t>(stream));
+    return step_impl(layer, x, B, y, mask_out, idx_out, nnz_out, w, static_cast<hipStream_t>(stream), nullptr);
 }
 
 svdp_status svdp_ffn_step_glued(const svdp_layer *layer, const void *x_prev, const float *y_prev, const float *shift,
@@ -608,7 +542,7 @@ svdp_status svdp_ffn_step_glued(const svdp_layer *layer, const void *x_prev, con
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
     const GlueArgs glue{y_prev, shift, eps, x_out};
-    return dispatch_step(layer, x_prev, B, y, mask_out, idx_out, nnz_out, w, ws, static_cast<hipStream_t>(stream), &glue);
+    return step_impl(layer, x_prev, B, y, mask_out, idx_out, nnz_out, w, static_cast<hipStream_t>(stream), &glue);
 }
 
 svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask, void *ws,
@@ -620,7 +554,13 @@ svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, 
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
-    return dispatch_rows_only(layer, x, B, mask, w, static_cast<hipStream_t>(stream));
+    return dispatch(layer->wdtype, nb_of(B), [&](auto wt, auto nb) -> svdp_status {
+        using W = typename decltype(wt)::type;
+        constexpr int NB = decltype(nb)::value;
+        if (!prepare_rows<W, NB, ROWS_MASK>(layer)) return SVDP_ERR_UNSUPPORTED;
+        return launch_rows_only<W, NB, ROWS_MASK>(layer, x, B, mask, nullptr, nullptr, nullptr, nullptr, w,
+                                                  static_cast<hipStream_t>(stream));
+    });
 }
 
 svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift, int32_t d, int32_t dtype, float eps,
@@ -635,11 +575,9 @@ svdp_status svdp_stack_glue(const void *x, const float *y, const float *shift, i
     if (dtype == SVDP_F32)
         hipLaunchKernelGGL(k_stack_glue<float>, dim3(1), dim3(256), 0, st, static_cast<const float *>(x), y, shift,
                            d, eps, static_cast<float *>(x_next));
-    else if (dtype == SVDP_BF16)
+    else
         hipLaunchKernelGGL(k_stack_glue<bf16>, dim3(1), dim3(256), 0, st, static_cast<const bf16 *>(x), y, shift, d,
                            eps, static_cast<bf16 *>(x_next));
-    else
-        return SVDP_ERR_UNSUPPORTED;
     return hip_status(hipSuccess);
 }
 
@@ -661,6 +599,18 @@ size_t svdp_calib_workspace_bytes(int32_t D, int32_t T, int32_t eta)
     const size_t MS = ((size_t)T + eta - 1) / eta;
     return align_up((size_t)D * MS * 4) + 2 * align_up((size_t)D * (MS + 1) * 4) + align_up((size_t)D * 4) +
            align_up(sizeof(SelectState)) + align_up((size_t)SEL_BINS * 8) + 2 * align_up((size_t)D * 4);
+}
+
+int64_t svdp_calib_need(double sparsity, int32_t D, int32_t T)
+{
+    if (D < 1 || T < 1 || std::isnan(sparsity)) return -1;
+    const int64_t all = (int64_t)D * (int64_t)T;
+    const double target = sparsity * (double)D * (double)T;         // (sparsity * D) * T, in double
+    if (!(target > 0.0)) return 0;
+    if (target >= (double)all) return all;
+    int64_t n = (int64_t)std::ceil(target);
+    while (n > 0 && (double)(n - 1) >= target) --n;
+    return n < 0 ? 0 : n > all ? all : n;
 }
 
 svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
@@ -685,8 +635,7 @@ svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T
     int n2 = 1;
     while (n2 < T) n2 <<= 1;
     const size_t lds = (size_t)n2 * 8 + (size_t)T * 8 + (size_t)(MS + 1) * 8;
-    static int granted = 64 * 1024;
-    if (allow_lds(k_calib_sort, lds, &granted) != hipSuccess) return SVDP_ERR_UNSUPPORTED;
+    if (!grant_lds<k_calib_sort>(lds)) return SVDP_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(k_calib_sort, dim3(D), dim3(CAL_THREADS), lds, st, w, s, T, n2, eta, MS, key, drop, tauc, k0,
                        kendall);
     svdp_status e = hip_status(hipSuccess);
@@ -761,48 +710,6 @@ svdp_status svdp_calib_stats(const svdp_layer *layer, const void *X, int32_t T, 
     return hip_status(hipSuccess);
 }
 
-const char *svdp_version(void) { return "0.3"; }
-
-void svdp_set_step_mode(int32_t mode, int32_t spin_limit)
-{
-    if (mode >= SVDP_STEP_SEQUENCE && mode <= SVDP_STEP_MERGED_REDUCE) g_fused_mode.store(mode);
-    if (spin_limit > 0) g_spin_limit.store(spin_limit);
-}
-
-void svdp_set_engine(int32_t engine)
-{
-    if (engine >= SVDP_ENGINE_AUTO && engine <= SVDP_ENGINE_MATRIX) g_engine.store(engine);
-}
-
-svdp_status svdp_step_timeouts(int32_t *count)
-{
-    if (count == nullptr) return SVDP_ERR_INVALID_ARG;
-    *count = 0;
-    std::lock_guard<std::mutex> lock(g_slot_mutex);
-    if (g_ctrl_base == nullptr) return SVDP_OK;          // the persistent kernel never ran
-    if (hipDeviceSynchronize() != hipSuccess) return SVDP_ERR_HIP;
-    for (size_t i = 0; i < g_slots.size(); ++i) {
-        uint32_t flag = 0;
-        uint32_t *p = g_ctrl_base + i * CTRL_WORDS + CTRL_ERROR;
-        if (hipMemcpy(&flag, p, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return SVDP_ERR_HIP;
-        if (flag != 0) {
-            *count += 1;
-            flag = 0;
-            if (hipMemcpy(p, &flag, sizeof(flag), hipMemcpyHostToDevice) != hipSuccess) return SVDP_ERR_HIP;
-        }
-    }
-    return SVDP_OK;
-}
-
-#ifdef SVDP_TRACE
-// Debug builds only: copy the phase time stamps to the host (synchronises).
-int svdp_debug_read_trace(unsigned long long *host, size_t count)
-{
-    const size_t total = sizeof(svdp::g_trace) / sizeof(svdp::g_trace[0]);
-    if (count > total) count = total;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(svdp::g_trace), count * sizeof(unsigned long long), 0,
-                                    hipMemcpyDeviceToHost);
-}
-#endif
+const char *svdp_version(void) { return "0.4"; }
 
 }  // extern "C"

@@ -7,32 +7,6 @@
 
 namespace svdp {
 
-// Optional phase time stamps (debug builds with -DSVDP_TRACE only): lane 0 of every
-// block records the 100 MHz real-time counter at numbered points of a kernel.
-#ifdef SVDP_TRACE
-constexpr int TRACE_SLOTS = 8;
-constexpr int TRACE_BLOCKS = 512;
-constexpr int TRACE_KERNELS = 4;
-__device__ unsigned long long g_trace[TRACE_KERNELS * TRACE_BLOCKS * TRACE_SLOTS];
-#define SVDP_STAMP(kernel_id, slot)                                                                   \
-    do {                                                                                              \
-        if (threadIdx.x == 0 && blockIdx.x < TRACE_BLOCKS && blockIdx.y == 0)                         \
-            g_trace[((kernel_id)*TRACE_BLOCKS + blockIdx.x) * TRACE_SLOTS + (slot)] = wall_clock64(); \
-    } while (0)
-#define SVDP_STAMP_CLK(kernel_id, slot)                                                               \
-    do {                                                                                              \
-        if (threadIdx.x == 0 && blockIdx.x < TRACE_BLOCKS && blockIdx.y == 0)                         \
-            g_trace[((kernel_id)*TRACE_BLOCKS + blockIdx.x) * TRACE_SLOTS + (slot)] = clock64();      \
-    } while (0)
-#else
-#define SVDP_STAMP_CLK(kernel_id, slot) \
-    do {                                \
-    } while (0)
-#define SVDP_STAMP(kernel_id, slot) \
-    do {                            \
-    } while (0)
-#endif
-
 // bfloat16 storage element (bit pattern only; all arithmetic is fp32, the
 // "full precision registers, half precision memory" policy of the paper's App. C).
 struct bf16 {
@@ -107,6 +81,7 @@ __device__ __forceinline__ void widen(const uint4 &q, float (&v)[8], const bf16 
 // bf16: four packed two-element dot instructions (bf16 x bf16 products are exact in
 // fp32; the sum is rounded to fp32); fp32: four fused multiply-adds.
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float dot_raw(const uint4 &w, const uint4 &x, float acc, const float *)
 {
     acc = fmaf(__uint_as_float(w.x), __uint_as_float(x.x), acc);

@@ -6,7 +6,6 @@
 #pragma once
 
 #include "svdp_device.h"
-#include "svdp_sync.h"
 
 namespace svdp {
 
@@ -16,7 +15,7 @@ constexpr int XP_COLS = 32;          // columns of P per k_xP block
 constexpr int SC_SLAB = 64;          // neurons per k_scores block = one mask word
 constexpr int ROWS_THREADS = 512;    // k_rows block
 constexpr int ROWS_WAVES = ROWS_THREADS / 64;
-constexpr int ROWS_UB = 4;           // k_rows: rows of W_downT fetched together (chunk padded to this)
+constexpr int ROWS_UB = 4;           // row kernels: rows of W_downT fetched together (the LDS row capacity is padded to this)
 constexpr int SCAN_THREADS = 1024;   // k_compact_scan block
 constexpr int RED_COLS = 8;          // k_reduce_y: float4 columns per block (one 128-byte line per partial row)
 constexpr int RED_SEGS = 64;         // k_reduce_y: segments of the partial list per block
@@ -93,7 +92,6 @@ __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, cons
     const int cgi = tid % CG, sub = tid / CG;
     const int col = c0 + cgi * VEC;
     const bool colok = col < r;
-    SVDP_STAMP(0, 0);
 
     uint4 raw[RPT];
 #pragma unroll
@@ -188,7 +186,6 @@ __global__ __launch_bounds__(XP_THREADS) void k_xP(const W *__restrict__ P, cons
             tpart[((size_t)blockIdx.x * NB + b) * r + c0 + k] = t;
         }
     }
-    SVDP_STAMP(0, 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -240,7 +237,6 @@ __global__ __launch_bounds__(SC_THREADS) void k_scores(const W *__restrict__ Q,
     const int lig = tid & (LPR - 1);
     const int grp = tid >> LPR_LOG2;
     const int cg = r / VEC;
-    SVDP_STAMP(1, 0);
     const float my_bias = tid < SC_SLAB ? bias[i0 + tid] : 0.f;     // added after the row sums
 
     // first column group of each of this group's rows
@@ -277,7 +273,6 @@ __global__ __launch_bounds__(SC_THREADS) void k_scores(const W *__restrict__ Q,
         }
         __syncthreads();
     }
-    SVDP_STAMP(1, 1);
 
     float acc[RPG][NB];
 #pragma unroll
@@ -335,7 +330,6 @@ __global__ __launch_bounds__(SC_THREADS) void k_scores(const W *__restrict__ Q,
         const uint64_t m = __ballot(on);
         if (tid == 0) mask_out[blockIdx.x] = m;
     }
-    SVDP_STAMP(1, 2);
 }
 
 // ---------------------------------------------------------------------------
@@ -415,17 +409,20 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_compact_scan(const uint64_t *_
 //            h * W_downT[i][cols] over the chunk in list order -> ypart[g].
 //            The first rows of W_downT are requested before phase A starts.
 // Blocks with an empty chunk write nothing; block 0 records n for k_reduce_y.
-// With FINISH the kernel also performs k_reduce_y's sum inside the same launch
-// (partials written through to memory, a counter per group of blocks, a bounded
-// wait, then each block sums a 128-byte column slice); every block of the
-// launch must then be resident at once.  Measured slower than the separate
-// launch, so it is an option only.
 // max_chunk (the LDS row capacity) is a multiple of ROWS_UB.
 // Dynamic LDS: NB*d storage elements (x as stored), NB*max_chunk floats, max_chunk ints.
 // ---------------------------------------------------------------------------
 enum RowsMode { ROWS_DENSE = 0, ROWS_LIST = 1, ROWS_MASK = 2 };
 
-__device__ __forceinline__ int chunk_of(int n, int G) { return (n + G - 1) / G; }
+// Rows per block: the list of n rows is cut into contiguous chunks of
+// max(min_chunk, ceil(n / G)) rows, so that a short list occupies fewer blocks and leaves
+// fewer partial y's to write and sum.  (Spreading a list of ~1000 rows of the 7B shape over every
+// compute unit is 0.3 us faster in the row kernel than four rows per block and 1.3 us faster than
+// eight, measured; four costs the step nothing, because the sum of the partials gains what the
+// row kernel loses, and halves the partial-y traffic of short lists.)
+__device__ __forceinline__ int chunk_of(int n, int G, int min_chunk) { return max(min_chunk, (n + G - 1) / G); }
+// Blocks that get rows (= partial y's written).
+__device__ __forceinline__ int active_blocks(int n, int chunk) { return n > 0 ? (n + chunk - 1) / chunk : 0; }
 
 // Length n of the row list.  ROWS_MASK: every wave scans the popcounts of all mask words
 // by itself (lane l owns the wpl consecutive words starting at l*wpl), so no block-wide
@@ -497,13 +494,34 @@ __device__ __forceinline__ void rows_list_from_mask(int D, const uint64_t *__res
     }
 }
 
-template <typename W, int NB, int MODE, bool FINISH>
+// This block's part of the row list into lidx[0 .. cnt): from the caller's list (entries outside
+// [0, D) become -1 and are skipped by every row kernel: they contribute nothing), from the mask
+// words (wave 0), or the block's own range of all rows.  Ends with a block barrier.
+template <int MODE>
+__device__ __forceinline__ void rows_block_list(int D, const uint64_t *__restrict__ mask,
+                                                const int32_t *__restrict__ idx_in, int lane_first, int wpl,
+                                                const uint64_t (&held)[ROWS_WREG], int lo, int hi, int *lidx)
+{
+    const int tid = threadIdx.x, cnt = hi - lo;
+    if (MODE == ROWS_LIST) {
+        for (int q = tid; q < cnt; q += blockDim.x) {
+            const int i = idx_in[lo + q];
+            lidx[q] = (unsigned)i < (unsigned)D ? i : -1;
+        }
+    } else if (MODE == ROWS_MASK) {
+        if (tid < 64) rows_list_from_mask(D, mask, tid, lane_first, wpl, held, lo, hi, lidx);
+    } else {
+        for (int q = tid; q < cnt; q += blockDim.x) lidx[q] = lo + q;
+    }
+    __syncthreads();
+}
+
+template <typename W, int NB, int MODE>
 __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4))) void k_rows(
     const W *__restrict__ Wg, const W *__restrict__ Wu, const W *__restrict__ WdT, const W *__restrict__ x, int B,
     int d, int D, const uint64_t *__restrict__ mask, const int32_t *__restrict__ idx_in,
     const int32_t *__restrict__ nnz_in, int32_t *__restrict__ idx_out, int32_t *__restrict__ nnz_out,
-    int32_t *__restrict__ n_used, int max_chunk, uint32_t flags, float *ypart, float *__restrict__ y,
-    uint32_t *ctrl, int spin_limit)
+    int32_t *__restrict__ n_used, int max_chunk, int min_chunk, uint32_t flags, float *__restrict__ ypart)
 {
     constexpr int VEC = Elem<W>::VEC;
     constexpr int UA = NB <= 2 ? 8 : 4;     // 16-byte loads in flight per matrix in phase A
@@ -515,8 +533,6 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
     int *lidx = reinterpret_cast<int *>(hs + NB * max_chunk);    // [max_chunk]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int G = gridDim.x;
-    SVDP_STAMP(2, 0);
-    SVDP_STAMP_CLK(2, 6);
 
     // ---- request x (as stored, no conversion; rows of a batch beyond B are zero).  The first
     // vector of every token stays in registers until the list is known, so that the request
@@ -530,97 +546,98 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
     int lane_first, wpl;
     uint64_t held[ROWS_WREG];
     const int n = rows_list_length<MODE>(D, mask, nnz_in, lane, lane_first, wpl, held);
-    SVDP_STAMP(2, 1);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (tid < nvec) xraw[b * nvec + tid] = xfirst[b];
         for (int v = tid + ROWS_THREADS; v < nvec; v += ROWS_THREADS)
             xraw[b * nvec + v] = b < B ? load_raw(x + (size_t)b * d + (size_t)v * VEC) : make_uint4(0u, 0u, 0u, 0u);
     }
-    const int chunk = chunk_of(n, G);
+    const int chunk = chunk_of(n, G, min_chunk);
     const int lo = min(n, (int)blockIdx.x * chunk);
     const int hi = min(n, lo + chunk);
     const int cnt = hi - lo;
     if (blockIdx.x == 0 && tid == 0) {
-        if (MODE != ROWS_DENSE && !FINISH) *n_used = n;
+        if (MODE != ROWS_DENSE) *n_used = n;
         if (MODE == ROWS_MASK && nnz_out != nullptr) *nnz_out = n;
     }
-    if (!FINISH && cnt <= 0) return;
+    if (cnt <= 0) return;
 
-    if (cnt > 0) {
-    // Phase B walks the chunk in groups of UB rows; the last group is padded with
-    // repeats of the last row whose h is 0, so no loop below needs a tail.
+    // h of the positions past the chunk's end (phase B works in whole groups of UB rows)
     const int ngroups = (cnt + UB - 1) / UB;
-    const int padded = ngroups * UB;
-    if (MODE == ROWS_LIST) {
-        for (int q = tid; q < padded; q += ROWS_THREADS) lidx[q] = idx_in[lo + min(q, cnt - 1)];
-    } else if (MODE == ROWS_MASK) {
-        if (wave == 0) {
-            rows_list_from_mask(D, mask, lane, lane_first, wpl, held, lo, hi, lidx);
-            // same wave, LDS is in order: the last real entry is visible to the padding
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            if (lane < padded - cnt) lidx[cnt + lane] = lidx[cnt - 1];
-        }
-    }
-    for (int i = cnt + tid; i < padded; i += ROWS_THREADS)
+    for (int i = cnt + tid; i < ngroups * UB; i += ROWS_THREADS)
 #pragma unroll
         for (int b = 0; b < NB; ++b) hs[b * max_chunk + i] = 0.f;
-    __syncthreads();
-    SVDP_STAMP(2, 2);
+    rows_block_list<MODE>(D, mask, idx_in, lane_first, wpl, held, lo, hi, lidx);
     if (MODE == ROWS_MASK && idx_out != nullptr)
         for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
 
     const bool drelu = (flags & 1u) != 0;
-    // the sequential pipeline has its own kernel (k_rows_seq); here only the in-launch-reduction variant skips rows
-    const bool revalidate = FINISH && (flags & 2u) != 0;
-    auto row_of = [&](int q) -> size_t {
-        return MODE == ROWS_DENSE ? (size_t)(lo + min(q, cnt - 1)) : (size_t)lidx[q];
+    // row q of the chunk, or -1 (past the end; a rejected entry of the caller's list)
+    auto row_of = [&](int q) -> int { return q < cnt ? (MODE == ROWS_DENSE ? lo + q : lidx[q]) : -1; };
+    auto down_piece = [&](int q, const W *colp) -> uint4 {      // the same branch for every thread of the block
+        const int row = row_of(q);
+        uint4 piece = make_uint4(0u, 0u, 0u, 0u);
+        if (row >= 0) piece = load_raw(colp + (size_t)row * d);
+        return piece;
     };
 
     // ---- request the first group of W_downT rows for this thread's first column group ----
     uint4 cur[UB];
-    const bool preload = !revalidate && tid < nvec;
-    if (preload) {
+    if (tid < nvec) {
 #pragma unroll
-        for (int k = 0; k < UB; ++k) cur[k] = load_raw(WdT + row_of(k) * d + (size_t)tid * VEC);
+        for (int k = 0; k < UB; ++k) cur[k] = down_piece(k, WdT + (size_t)tid * VEC);
     }
 
-    // ---- phase A ----
-    const int nfull = nvec / (64 * UA);
+    // ---- phase A: one wave per row; the row's 16-byte vectors are fetched UA at a time per
+    // matrix and lane (the whole row at once when d <= 64*UA*VEC) ----
     for (int q = wave; q < cnt; q += ROWS_WAVES) {
-        const size_t row = row_of(q);
-        const W *g = Wg + row * d + (size_t)lane * VEC;
-        const W *u = Wu + row * d + (size_t)lane * VEC;
+        const int row = row_of(q);
         float ag[NB], au[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) ag[b] = au[b] = 0.f;
-        for (int it = 0; it < nfull; ++it) {
-            uint4 rg[UA], ru[UA];
+        if (row >= 0) {
+            const W *g = Wg + (size_t)row * d;
+            const W *u = Wu + (size_t)row * d;
+            // whole batches of UA vectors per matrix and lane, then one batch with a ragged end
+            int vb = 0;
+            for (; vb + 64 * UA <= nvec; vb += 64 * UA) {
+                uint4 rg[UA], ru[UA];
 #pragma unroll
-            for (int k = 0; k < UA; ++k) {
-                rg[k] = load_raw(g + (size_t)(it * UA + k) * 64 * VEC);
-                ru[k] = load_raw(u + (size_t)(it * UA + k) * 64 * VEC);
-            }
+                for (int k = 0; k < UA; ++k) {
+                    rg[k] = load_raw(g + (size_t)(vb + k * 64 + lane) * VEC);
+                    ru[k] = load_raw(u + (size_t)(vb + k * 64 + lane) * VEC);
+                }
 #pragma unroll
-            for (int k = 0; k < UA; ++k) {
-                const int v = lane + (it * UA + k) * 64;
+                for (int k = 0; k < UA; ++k) {
 #pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    const uint4 xv = xraw[b * nvec + v];
-                    ag[b] = dot_raw(rg[k], xv, ag[b], (const W *)nullptr);
-                    au[b] = dot_raw(ru[k], xv, au[b], (const W *)nullptr);
+                    for (int b = 0; b < NB; ++b) {
+                        const uint4 xv = xraw[b * nvec + vb + k * 64 + lane];
+                        ag[b] = dot_raw(rg[k], xv, ag[b], (const W *)nullptr);
+                        au[b] = dot_raw(ru[k], xv, au[b], (const W *)nullptr);
+                    }
                 }
             }
-        }
-        for (int v = lane + nfull * UA * 64; v < nvec; v += 64) {       // ragged tail of the row
-            const uint4 rg = load_raw(Wg + row * d + (size_t)v * VEC);
-            const uint4 ru = load_raw(Wu + row * d + (size_t)v * VEC);
+            if (vb < nvec) {
+                uint4 rg[UA], ru[UA];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const uint4 xv = xraw[b * nvec + v];
-                ag[b] = dot_raw(rg, xv, ag[b], (const W *)nullptr);
-                au[b] = dot_raw(ru, xv, au[b], (const W *)nullptr);
+                for (int k = 0; k < UA; ++k) {
+                    const int v = vb + k * 64 + lane;
+                    rg[k] = ru[k] = make_uint4(0u, 0u, 0u, 0u);
+                    if (v < nvec) {
+                        rg[k] = load_raw(g + (size_t)v * VEC);
+                        ru[k] = load_raw(u + (size_t)v * VEC);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < UA; ++k) {
+                    const int v = min(vb + k * 64 + lane, nvec - 1);      // a zero weight vector meets any x
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        const uint4 xv = xraw[b * nvec + v];
+                        ag[b] = dot_raw(rg[k], xv, ag[b], (const W *)nullptr);
+                        au[b] = dot_raw(ru[k], xv, au[b], (const W *)nullptr);
+                    }
+                }
             }
         }
 #pragma unroll
@@ -630,15 +647,13 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
             if (lane == 0) {
                 const float gp = fmaxf(gs, 0.f);
                 const float uu = drelu ? fmaxf(us, 0.f) : us;
-                hs[b * max_chunk + q] = gp * uu;
+                hs[b * max_chunk + q] = row >= 0 ? gp * uu : 0.f;
             }
         }
     }
-    SVDP_STAMP(2, 3);
     __syncthreads();
-    SVDP_STAMP(2, 4);
 
-    // ---- phase B ----
+    // ---- phase B: every thread owns 16-byte column groups of the output ----
     for (int v = tid; v < nvec; v += ROWS_THREADS) {
         float acc[NB][VEC];
 #pragma unroll
@@ -646,146 +661,47 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[b][e] = 0.f;
         const W *colp = WdT + (size_t)v * VEC;
-        if (revalidate) {
-            // sequential pipeline: a row whose gate was <= 0 for every token is not read
-            for (int q = 0; q < cnt; ++q) {
-                float h[NB];
-                bool any = false;
+        if (v != tid) {
+#pragma unroll
+            for (int k = 0; k < UB; ++k) cur[k] = down_piece(k, colp);
+        }
+        for (int gq = 0; gq < ngroups; ++gq) {
+            uint4 nxt[UB];
+            if (gq + 1 < ngroups) {
+#pragma unroll
+                for (int k = 0; k < UB; ++k) nxt[k] = down_piece((gq + 1) * UB + k, colp);
+            }
+#pragma unroll
+            for (int k = 0; k < UB; ++k) {
+                float w[VEC];
+                widen(cur[k], w, (const W *)nullptr);
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    h[b] = hs[b * max_chunk + q];
-                    any = any || (h[b] != 0.f);
+                    const float h = hs[b * max_chunk + gq * UB + k];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc[b][e] = fmaf(h, w[e], acc[b][e]);
                 }
-                if (!any) continue;
-                float w[VEC];
-                load_vec(colp + row_of(q) * d, w);
-#pragma unroll
-                for (int b = 0; b < NB; ++b)
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) acc[b][e] = fmaf(h[b], w[e], acc[b][e]);
             }
-        } else {
-            if (v != tid) {
 #pragma unroll
-                for (int k = 0; k < UB; ++k) cur[k] = load_raw(colp + row_of(k) * d);
-            }
-            for (int gq = 0; gq < ngroups; ++gq) {
-                uint4 nxt[UB];
-                if (gq + 1 < ngroups) {
-#pragma unroll
-                    for (int k = 0; k < UB; ++k) nxt[k] = load_raw(colp + row_of((gq + 1) * UB + k) * d);
-                }
-#pragma unroll
-                for (int k = 0; k < UB; ++k) {
-                    float w[VEC];
-                    widen(cur[k], w, (const W *)nullptr);
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        const float h = hs[b * max_chunk + gq * UB + k];
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) acc[b][e] = fmaf(h, w[e], acc[b][e]);
-                    }
-                }
-#pragma unroll
-                for (int k = 0; k < UB; ++k) cur[k] = nxt[k];
-            }
+            for (int k = 0; k < UB; ++k) cur[k] = nxt[k];
         }
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            float *outf = ypart + ((size_t)blockIdx.x * NB + b) * d + (size_t)v * VEC;
-            if (FINISH) {
-                // other blocks of this launch read it: written through to memory
+            float4 *out = reinterpret_cast<float4 *>(ypart + ((size_t)blockIdx.x * NB + b) * d + (size_t)v * VEC);
 #pragma unroll
-                for (int e4 = 0; e4 < VEC / 4; ++e4)
-                    store_wt16(outf + 4 * e4, acc[b][4 * e4], acc[b][4 * e4 + 1], acc[b][4 * e4 + 2], acc[b][4 * e4 + 3]);
-            } else {
-                float4 *out = reinterpret_cast<float4 *>(outf);
-#pragma unroll
-                for (int e4 = 0; e4 < VEC / 4; ++e4)
-                    out[e4] = make_float4(acc[b][4 * e4], acc[b][4 * e4 + 1], acc[b][4 * e4 + 2], acc[b][4 * e4 + 3]);
-            }
-        }
-    }
-    }   // cnt > 0
-    SVDP_STAMP(2, 5);
-    SVDP_STAMP_CLK(2, 7);
-    if (!FINISH) return;
-
-    // ---- second stage of the down-projection reduction inside the same launch:
-    // y[b][cols] = sum over the blocks that had rows, for 128-byte column slices ----
-    wait_stores_done();
-    __syncthreads();
-    if (tid == 0) signal(ctrl, CTRL_Y, blockIdx.x);
-    wait_stage(ctrl, CTRL_Y, G, spin_limit);
-    {
-        constexpr int RC = 8, RS = ROWS_THREADS / RC;               // float4 columns x segments of partials
-        float4 *red = reinterpret_cast<float4 *>(smem16);           // [RS][RC]
-        const int gact = n > 0 ? (n + chunk - 1) / chunk : 0;
-        const int vpt = d / 4;
-        const int c = tid % RC, seg = tid / RC;
-        for (int cb = blockIdx.x; cb * RC < vpt; cb += G) {
-            const int v = cb * RC + c;
-            for (int b = 0; b < B; ++b) {
-                float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (v < vpt) {
-                    // the (at most G/RS = 4 per pass) partials of this thread, fetched together
-                    for (int g0 = seg; g0 < gact; g0 += 4 * RS) {
-                        const float *base = ypart + (size_t)b * d + (size_t)v * 4;
-                        const size_t gs = (size_t)NB * d;
-                        const int g1 = g0 + RS, g2 = g0 + 2 * RS, g3 = g0 + 3 * RS;
-                        f32x4_t p0, p1, p2, p3;
-                        load_wt16x4(base + g0 * gs, base + (g1 < gact ? g1 : g0) * gs, base + (g2 < gact ? g2 : g0) * gs,
-                                    base + (g3 < gact ? g3 : g0) * gs, p0, p1, p2, p3);
-                        s.x += p0.x; s.y += p0.y; s.z += p0.z; s.w += p0.w;
-                        if (g1 < gact) { s.x += p1.x; s.y += p1.y; s.z += p1.z; s.w += p1.w; }
-                        if (g2 < gact) { s.x += p2.x; s.y += p2.y; s.z += p2.z; s.w += p2.w; }
-                        if (g3 < gact) { s.x += p3.x; s.y += p3.y; s.z += p3.z; s.w += p3.w; }
-                    }
-                }
-                __syncthreads();
-                red[seg * RC + c] = s;
-                __syncthreads();
-                for (int cur = RS; cur > 1;) {                      // radix-4 tree, fixed order
-                    const int next = (cur + 3) / 4;
-                    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (seg < next) {
-                        t = red[(4 * seg) * RC + c];
-#pragma unroll
-                        for (int q = 1; q < 4; ++q) {
-                            if (4 * seg + q < cur) {
-                                const float4 p = red[(4 * seg + q) * RC + c];
-                                t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
-                            }
-                        }
-                    }
-                    __syncthreads();
-                    if (seg < next) red[seg * RC + c] = t;
-                    __syncthreads();
-                    cur = next;
-                }
-                if (seg == 0 && v < vpt) reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = red[c];
-            }
-        }
-    }
-    // the last block to leave zeroes the counters for the next launch
-    if (tid == 0) {
-        wait_stores_done();
-        const uint32_t old = __hip_atomic_fetch_add(ctrl + CTRL_EXIT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old == (uint32_t)G - 1u) {
-            for (int q = 0; q < CTRL_GROUPS; ++q)
-                __hip_atomic_store(ctrl + CTRL_Y + q * CTRL_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(ctrl + CTRL_EXIT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int e4 = 0; e4 < VEC / 4; ++e4)
+                out[e4] = make_float4(acc[b][4 * e4], acc[b][4 * e4 + 1], acc[b][4 * e4 + 2], acc[b][4 * e4 + 3]);
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// y[b][:] = sum over the blocks of k_rows that had work (second stage of the
-// deterministic down-projection reduction, App. C).
+// y[b][:] = sum over the blocks of the row kernel that had rows (second stage of
+// the deterministic down-projection reduction, App. C).
 // A block owns RED_COLS float4 columns (one 128-byte line) of one token; the list
 // of partials is cut into RED_SEGS contiguous segments summed by different
 // threads (all loads in flight at once); the eight segments of a wave are then
-// combined with lane shifts, the sixteen waves through LDS.  The order depends
+// combined with lane shifts, the eight waves through LDS.  The order depends
 // only on the number of partials.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float seg8_sum(float v)
@@ -798,16 +714,14 @@ __device__ __forceinline__ float seg8_sum(float v)
 
 __global__ __launch_bounds__(RED_COLS *RED_SEGS) void k_reduce_y(const float *__restrict__ ypart,
                                                                  const int32_t *__restrict__ n_ptr, int n_fixed,
-                                                                 int D, int G, int NB, int B, int d,
+                                                                 int D, int G, int min_chunk, int NB, int B, int d,
                                                                  float *__restrict__ y)
 {
     static_assert(RED_COLS == 8, "a wave holds 8 columns x 8 segments");
     __shared__ float4 wred[RED_COLS * RED_SEGS / 64][RED_COLS];
-    SVDP_STAMP(3, 0);
     int n = n_ptr != nullptr ? *n_ptr : n_fixed;
     n = max(0, min(n, D));
-    const int chunk = chunk_of(n, G);
-    const int gact = n > 0 ? (n + chunk - 1) / chunk : 0;
+    const int gact = active_blocks(n, chunk_of(n, G, min_chunk));
     const int vpt = d / 4;
     const int bpt = (vpt + RED_COLS - 1) / RED_COLS;
     const int b = blockIdx.x / bpt;
@@ -838,7 +752,6 @@ __global__ __launch_bounds__(RED_COLS *RED_SEGS) void k_reduce_y(const float *__
         }
         reinterpret_cast<float4 *>(y)[(size_t)b * vpt + v] = t;
     }
-    SVDP_STAMP(3, 1);
 }
 
 // ---------------------------------------------------------------------------

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
     const bf16 *__restrict__ Wg, const bf16 *__restrict__ Wu, const bf16 *__restrict__ WdT,
     const bf16 *__restrict__ x, int B, int d, int D, const uint64_t *__restrict__ mask,
     const int32_t *__restrict__ idx_in, const int32_t *__restrict__ nnz_in, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ nnz_out, int32_t *__restrict__ n_used, int max_chunk, uint32_t flags,
+    int32_t *__restrict__ nnz_out, int32_t *__restrict__ n_used, int max_chunk, int min_chunk, uint32_t flags,
     float *__restrict__ ypart)
 {
     static_assert(NB == 1 || NB == 2 || NB == 4 || NB == 8, "token slots are addressed with a mask");
@@ -63,7 +63,6 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lm = lane & 15, lq = lane >> 4;
     const int G = gridDim.x;
-    SVDP_STAMP(2, 0);
 
     // ---- request x; the vector of element 8c..8c+7 goes where the lane that needs it as an
     // operand will read it: step c/8, instruction (c/4)%2, lane quarter c%4, token ----
@@ -76,14 +75,13 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
     int lane_first, wpl;
     uint64_t held[ROWS_WREG];
     const int n = rows_list_length<MODE>(D, mask, nnz_in, lane, lane_first, wpl, held);
-    SVDP_STAMP(2, 1);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         if (tid < nvec) xs[xslot(tid, b)] = xfirst[b];
         for (int c = tid + ROWS_THREADS; c < nvec; c += ROWS_THREADS)
             xs[xslot(c, b)] = b < B ? load_raw(x + (size_t)b * d + (size_t)c * 8) : make_uint4(0u, 0u, 0u, 0u);
     }
-    const int chunk = chunk_of(n, G);
+    const int chunk = chunk_of(n, G, min_chunk);
     const int lo = min(n, (int)blockIdx.x * chunk);
     const int hi = min(n, lo + chunk);
     const int cnt = hi - lo;
@@ -93,21 +91,16 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
     }
     if (cnt <= 0) return;
 
-    if (MODE == ROWS_LIST) {
-        for (int q = tid; q < cnt; q += ROWS_THREADS) lidx[q] = idx_in[lo + q];
-    } else if (MODE == ROWS_MASK) {
-        if (wave == 0) rows_list_from_mask(D, mask, lane, lane_first, wpl, held, lo, hi, lidx);
-    }
-    __syncthreads();
-    SVDP_STAMP(2, 2);
+    rows_block_list<MODE>(D, mask, idx_in, lane_first, wpl, held, lo, hi, lidx);
     if (MODE == ROWS_MASK && idx_out != nullptr)
         for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
 
     const bool drelu = (flags & 1u) != 0;
-    // rows past the end of the chunk repeat its last row; their h is zero
+    // rows past the end of the chunk repeat its last row, and a rejected entry of the caller's list
+    // (-1) reads row 0 in its place; the h of both is zero
     auto row_of = [&](int q) -> size_t {
         const int qq = min(q, cnt - 1);
-        return MODE == ROWS_DENSE ? (size_t)(lo + qq) : (size_t)lidx[qq];
+        return MODE == ROWS_DENSE ? (size_t)(lo + qq) : (size_t)max(lidx[qq], 0);
     };
     const int ntile = (cnt + MF_ROWS - 1) / MF_ROWS;
 
@@ -169,13 +162,12 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
             if (++qi == cnt) { qi = 0; ++ji; }
         }
     }
-    SVDP_STAMP(2, 3);
     __syncthreads();
     // partial tiles of the waves, added in wave order -> h[row][token slot]
     for (int e = tid; e < ntile * MF_ROWS * MF_TOK; e += ROWS_THREADS) {
         const int q = e / MF_TOK, b = e % MF_TOK;
         float h = 0.f;
-        if (b < NB && q < cnt) {
+        if (b < NB && q < cnt && (MODE != ROWS_LIST || lidx[q] >= 0)) {
             const int t = q / MF_ROWS, rr = q % MF_ROWS;
             float gs = 0.f, us = 0.f;
 #pragma unroll
@@ -189,7 +181,6 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
         hs[e] = h;
     }
     __syncthreads();
-    SVDP_STAMP(2, 4);
 
     // ---- phase B: the wave's units are walked in one sequence, MF_UB of them fetched ahead, so
     // that the loads of the next column tile are in flight while the current one is finished.
@@ -254,7 +245,6 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
             for (int k = 0; k < MF_UB; ++k) cur[k] = nxt[k];
         }
     }
-    SVDP_STAMP(2, 5);
 }
 
 // ---------------------------------------------------------------------------
@@ -292,7 +282,6 @@ __global__ __launch_bounds__(SCM_THREADS) void k_scores_mfma(const bf16 *__restr
     const int lm = lane & 15, lq = lane >> 4;
     const int i0 = blockIdx.x * SC_SLAB + wave * 16;
     const int nkb = r / 32;
-    SVDP_STAMP(1, 0);
 
     uint4 q[SCM_KB];
     const bf16 *qrow = Q + (size_t)(i0 + lm) * r + lq * 8;
@@ -333,7 +322,6 @@ __global__ __launch_bounds__(SCM_THREADS) void k_scores_mfma(const bf16 *__restr
                            pl[p][6] | (pl[p][7] << 16));
     }
     __syncthreads();
-    SVDP_STAMP(1, 1);
 
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     const int tb = lm & (NB - 1);
@@ -366,7 +354,6 @@ __global__ __launch_bounds__(SCM_THREADS) void k_scores_mfma(const bf16 *__restr
             mask_out[blockIdx.x] = (uint64_t)word16[0] | ((uint64_t)word16[1] << 16) | ((uint64_t)word16[2] << 32) |
                                    ((uint64_t)word16[3] << 48);
     }
-    SVDP_STAMP(1, 2);
 }
 
 }   // namespace svdp

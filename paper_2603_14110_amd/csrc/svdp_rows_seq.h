@@ -25,11 +25,11 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
     const W *__restrict__ Wg, const W *__restrict__ Wu, const W *__restrict__ WdT, const W *__restrict__ x, int B,
     int d, int D, const uint64_t *__restrict__ mask, const int32_t *__restrict__ idx_in,
     const int32_t *__restrict__ nnz_in, int32_t *__restrict__ idx_out, int32_t *__restrict__ nnz_out,
-    int32_t *__restrict__ n_used, int max_chunk, uint32_t flags, float *__restrict__ ypart)
+    int32_t *__restrict__ n_used, int max_chunk, int min_chunk, uint32_t flags, float *__restrict__ ypart)
 {
     constexpr int VEC = Elem<W>::VEC;
     constexpr int UG = NB <= 2 ? 8 : 4;     // 16-byte loads of one matrix in flight per lane in phase G
-    constexpr int UB = ROWS_UB;
+    constexpr int UB = 4;                   // rows of W_downT per group in phase B
     extern __shared__ uint4 smem16[];
     __shared__ int ns_shared;
     const int nvec = d / VEC;
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
         for (int v = tid + ROWS_THREADS; v < nvec; v += ROWS_THREADS)
             xraw[b * nvec + v] = b < B ? load_raw(x + (size_t)b * d + (size_t)v * VEC) : make_uint4(0u, 0u, 0u, 0u);
     }
-    const int chunk = chunk_of(n, G);
+    const int chunk = chunk_of(n, G, min_chunk);
     const int lo = min(n, (int)blockIdx.x * chunk);
     const int hi = min(n, lo + chunk);
     const int cnt = hi - lo;
@@ -65,14 +65,7 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
     }
     if (cnt <= 0) return;
 
-    if (MODE == ROWS_LIST) {
-        for (int q = tid; q < cnt; q += ROWS_THREADS) lidx[q] = idx_in[lo + q];
-    } else if (MODE == ROWS_MASK) {
-        if (wave == 0) rows_list_from_mask(D, mask, lane, lane_first, wpl, held, lo, hi, lidx);
-    } else {
-        for (int q = tid; q < cnt; q += ROWS_THREADS) lidx[q] = lo + q;
-    }
-    __syncthreads();
+    rows_block_list<MODE>(D, mask, idx_in, lane_first, wpl, held, lo, hi, lidx);
     if (MODE == ROWS_MASK && idx_out != nullptr)
         for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
     const bool drelu = (flags & 1u) != 0;
@@ -121,14 +114,16 @@ __global__ __launch_bounds__(ROWS_THREADS) __attribute__((amdgpu_waves_per_eu(4)
     for (int q = wave; q < cnt; q += 2 * ROWS_WAVES) {
         const int q2 = q + ROWS_WAVES;
         const bool two = q2 < cnt;                               // uniform over the wave
-        const size_t rowa = (size_t)lidx[q], rowb = (size_t)lidx[two ? q2 : q];
+        // a rejected entry of the caller's list (-1) reads row 0 in its place and never survives
+        const int ia = lidx[q], ib = lidx[two ? q2 : q];
+        const size_t rowa = (size_t)max(ia, 0), rowb = (size_t)max(ib, 0);
         float ga[NB], gb[NB], ua[NB], ub[NB];
         row_dot2(Wg + rowa * d, Wg + rowb * d, two, ga, gb);
         bool alive_a = false, alive_b = false;
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            alive_a = alive_a || (b < B && ga[b] > 0.f);
-            alive_b = alive_b || (two && b < B && gb[b] > 0.f);
+            alive_a = alive_a || (ia >= 0 && b < B && ga[b] > 0.f);
+            alive_b = alive_b || (two && ib >= 0 && b < B && gb[b] > 0.f);
         }
         // both tests are uniform over the wave: the gates are wave sums
         if (alive_a && alive_b) {

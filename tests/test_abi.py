@@ -80,13 +80,50 @@ def test_validation_rejects_before_any_launch(svdp):
     assert L.svdp_sparse_ffn(ctypes.byref(l), 0x1000, 1, None, 0x1000, 0x1000, 0x1000, ws, None) == INVALID
     assert L.svdp_ffn_step(ctypes.byref(l), 0x1000, 1, None, None, None, None, 0x1000, ws, None) == INVALID
     bad = _layer(svdp)
-    bad.flags = 8
+    bad.flags = 16                                        # an unknown flag bit
     assert L.svdp_ffn_step(ctypes.byref(bad), 0x1000, 1, 0x1000, None, None, None, 0x1000, ws, None) == INVALID
-    assert L.svdp_compact(None, 1, 64, 0x1000, 0x1000, 0x1000, None) == INVALID
-    assert L.svdp_compact(0x1000, 1, 100, 0x1000, 0x1000, 0x1000, None) == UNSUPPORTED
+    bad.flags = svdp.FLAG_ENGINE_VECTOR | svdp.FLAG_ENGINE_MATRIX       # both engines at once
+    assert L.svdp_ffn_step(ctypes.byref(bad), 0x1000, 1, 0x1000, None, None, None, 0x1000, ws, None) == INVALID
+    assert L.svdp_workspace_bytes(ctypes.byref(bad), 1) == 0
+    # a batch of tokens that does not fit a compute unit's local memory next to the row kernel's scratch is
+    # refused before anything is enqueued, and the size query says so too
+    big = _layer(svdp, d=16384, D=4096, r=64, dt=0)
+    assert L.svdp_workspace_bytes(ctypes.byref(big), 8) == 0
+    assert L.svdp_workspace_bytes(ctypes.byref(big), 1) > 0
+    assert L.svdp_ffn_step(ctypes.byref(big), 0x1000, 8, 0x1000, None, None, None, 0x1000, 1 << 40, None) == UNSUPPORTED
+    assert L.svdp_dense_ffn(ctypes.byref(big), 0x1000, 8, 0x1000, 0x1000, 1 << 40, None) == UNSUPPORTED
+    assert L.svdp_compact(None, 1, 64, 0x1000, 0x1000, 0x1000, None, 0, None) == INVALID
+    assert L.svdp_compact(0x1000, 1, 100, 0x1000, 0x1000, 0x1000, None, 0, None) == UNSUPPORTED
     assert L.svdp_stack_glue(None, 0x1000, 0x1000, 64, 0, 1e-6, 0x1000, None) == INVALID
     assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, None, 0x1000, ws, None) == INVALID
     assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, 0x1000, 0x1000, 64, None) == WORKSPACE
+
+
+def test_library_has_no_process_wide_switches(svdp):
+    """Modes and engines travel in svdp_layer.flags: no setter (or any other call that changes later calls)
+    is exported, by the header or by the shared object."""
+    import subprocess
+
+    names = _declared()
+    assert not [n for n in names if "_set_" in n or n.endswith("_timeouts")]
+    out = subprocess.run(["nm", "-D", "--defined-only", svdp.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = sorted(set(re.findall(r"\b(svdp_[a-z_0-9]+)\b", out)))
+    assert exported == names, (exported, names)
+
+
+def test_calib_need_is_the_oracles_rule(svdp):
+    """svdp_calib_need against the oracle's required_drops on a grid incl. products that are not exact in
+    binary (0.7 * 10, 0.1 * 3 ...), the clamps and the invalid cases."""
+    import math
+    from fractions import Fraction
+
+    from oracle import calib
+
+    L = svdp.lib()
+    for D, T in ((1, 1), (10, 1), (3, 1), (7, 13), (11008, 2048), (64, 4096), (1000, 1000)):
+        for sp in (0.0, 0.1, 0.3, 0.5, 0.7, 0.85, 0.9, 0.95, 0.999, 1.0, 1.5, -0.2, 1 / 3, 2 / 3, 1e-12):
+            assert L.svdp_calib_need(sp, D, T) == calib.required_drops(sp, D, T), (sp, D, T)
+    assert L.svdp_calib_need(0.5, 0, 4) == -1 and L.svdp_calib_need(float("nan"), 4, 4) == -1
 
 
 def test_calibration_entry_points_validate_on_the_host(svdp):

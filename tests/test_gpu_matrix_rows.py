@@ -1,4 +1,4 @@
-"""GPU parity of the kernels on the matrix cores (svdp_set_engine) against the CPU
+"""GPU parity of the kernels on the matrix cores (SVDP_FLAG_ENGINE_MATRIX) against the CPU
 oracle: every entry point that runs them, on seeded random layers whose row chunks
 span several 16-row tiles with ragged ends, for every batch size and predictor rank."""
 import numpy as np
@@ -17,8 +17,7 @@ def env(oracle):
 
     assert torch.cuda.is_available(), "these tests need a GPU"
     binding.lib()
-    yield binding, torch, oracle
-    binding.set_engine(binding.ENGINE_AUTO)
+    return binding, torch, oracle
 
 
 class RandomLayer:
@@ -54,23 +53,24 @@ def test_matrix_engine_every_entry_point(env, shape):
     f = c.f
     s_or = oracle.predict(f["P"], f["Q"], c.b, c.X)
     results = {}
-    for engine in (binding.ENGINE_MATRIX, binding.ENGINE_VECTOR):
-        binding.set_engine(engine)
+    MATRIX, VECTOR = binding.FLAG_ENGINE_MATRIX, binding.FLAG_ENGINE_VECTOR
+    for engine in (MATRIX, VECTOR):
+        dev = c.dev.with_flags(engine)
         # the whole step
         mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
         idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
         nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
-        y = binding.ffn_step(c.dev, c.Xd, mask=mask, idx=idx, nnz=nnz)
+        y = binding.ffn_step(dev, c.Xd, mask=mask, idx=idx, nnz=nnz)
         lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
         y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X, lst)
         parity.check_y(y.cpu().numpy(), y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X, lst))
-        assert torch.equal(y, binding.ffn_step(c.dev, c.Xd))            # optional outputs change nothing
+        assert torch.equal(y, binding.ffn_step(dev, c.Xd))              # optional outputs change nothing
         # dense baseline
-        yd = binding.dense_ffn(c.dev, c.Xd)
+        yd = binding.dense_ffn(dev, c.Xd)
         parity.check_y(yd.cpu().numpy(), oracle.dense_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X), "bf16",
                        slack=parity.fp32_forward_bound(f, c.X, np.arange(D)))
         # dReLU variant
-        dl = c.dev.with_flags(binding.FLAG_DRELU)
+        dl = c.dev.with_flags(binding.FLAG_DRELU | engine)
         mask2 = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
         idx2 = torch.full((D,), -1, dtype=torch.int32, device="cuda")
         nnz2 = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -81,11 +81,10 @@ def test_matrix_engine_every_entry_point(env, shape):
                        slack=parity.fp32_forward_bound(f, c.X, lst2))
         results[engine] = (lst, y.cpu().numpy(), yd.cpu().numpy())
     # the two engines: same list, y equal to fp32 rounding
-    assert np.array_equal(results[binding.ENGINE_MATRIX][0], results[binding.ENGINE_VECTOR][0])
+    assert np.array_equal(results[MATRIX][0], results[VECTOR][0])
     for k in (1, 2):
-        a, b = results[binding.ENGINE_MATRIX][k].astype(np.float64), results[binding.ENGINE_VECTOR][k].astype(np.float64)
+        a, b = results[MATRIX][k].astype(np.float64), results[VECTOR][k].astype(np.float64)
         assert np.linalg.norm(a - b) <= 2e-5 * max(np.linalg.norm(b), 1e-30)
-    binding.set_engine(binding.ENGINE_AUTO)
 
 
 @pytest.mark.parametrize("shape", SHAPES[1:4])
@@ -100,20 +99,17 @@ def test_matrix_engine_arbitrary_lists(env, shape):
              np.sort(rng.choice(D, 255, replace=False)).astype(np.int32),          # fewer rows than blocks
              np.sort(rng.choice(D, 257, replace=False)).astype(np.int32),
              rng.permutation(D)[: D // 7].astype(np.int32)]                        # unsorted lists are allowed
-    binding.set_engine(binding.ENGINE_MATRIX)
-    try:
-        for Bq in (1, 2, 3, 4, 8):
-            for lst in lists:
-                idx = torch.zeros(D, dtype=torch.int32, device="cuda")
-                idx[: lst.size] = torch.from_numpy(lst).cuda()
-                nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
-                y = binding.sparse_ffn(c.dev, c.Xd[:Bq], idx, nnz).cpu().numpy()
-                y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X[:Bq], lst)
-                parity.check_y(y, y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X[:Bq], lst))
-                if lst.size == 0:
-                    assert not y.any()
-    finally:
-        binding.set_engine(binding.ENGINE_AUTO)
+    dev = c.dev.with_flags(binding.FLAG_ENGINE_MATRIX)
+    for Bq in (1, 2, 3, 4, 8):
+        for lst in lists:
+            idx = torch.zeros(D, dtype=torch.int32, device="cuda")
+            idx[: lst.size] = torch.from_numpy(lst).cuda()
+            nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
+            y = binding.sparse_ffn(dev, c.Xd[:Bq], idx, nnz).cpu().numpy()
+            y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X[:Bq], lst)
+            parity.check_y(y, y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X[:Bq], lst))
+            if lst.size == 0:
+                assert not y.any()
 
 
 # (d, D, r, B): ranks the score kernel on the matrix cores takes (multiples of 32 up to 512) and two it does not
@@ -129,57 +125,83 @@ def test_matrix_engine_scores(env, shape):
     c = RandomLayer(binding, torch, 31 + r, d, D, r, B)
     f = c.f
     s_or = oracle.predict(f["P"], f["Q"], c.b, c.X)
-    binding.set_engine(binding.ENGINE_MATRIX)
-    try:
-        for Bq in sorted({1, B}):
-            s = binding.predict(c.dev, c.Xd[:Bq]).cpu().numpy().astype(np.float64)
-            assert s.shape == (Bq, D)
-            assert np.all(np.abs(s - s_or[:Bq]) <= 2e-5 * np.abs(s_or[:Bq]).max(axis=1, keepdims=True))
-            mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
-            idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
-            nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
-            y = binding.ffn_step(c.dev, c.Xd[:Bq], mask=mask, idx=idx, nnz=nnz)
-            lst = parity.check_mask_and_idx(s_or[:Bq], mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
-            y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X[:Bq], lst)
-            parity.check_y(y.cpu().numpy(), y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X[:Bq], lst))
-            # svdp_compact on the materialised scores gives the step's list
-            m2, i2, n2 = binding.compact(binding.predict(c.dev, c.Xd[:Bq]))
-            assert torch.equal(m2, mask) and n2.item() == nnz.item()
-            assert torch.equal(i2[: nnz.item()], idx[: nnz.item()])
-    finally:
-        binding.set_engine(binding.ENGINE_AUTO)
+    dev = c.dev.with_flags(binding.FLAG_ENGINE_MATRIX)
+    for Bq in sorted({1, B}):
+        s = binding.predict(dev, c.Xd[:Bq]).cpu().numpy().astype(np.float64)
+        assert s.shape == (Bq, D)
+        assert np.all(np.abs(s - s_or[:Bq]) <= 2e-5 * np.abs(s_or[:Bq]).max(axis=1, keepdims=True))
+        mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+        idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+        nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+        y = binding.ffn_step(dev, c.Xd[:Bq], mask=mask, idx=idx, nnz=nnz)
+        lst = parity.check_mask_and_idx(s_or[:Bq], mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+        y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], c.X[:Bq], lst)
+        parity.check_y(y.cpu().numpy(), y_ref, "bf16", slack=parity.fp32_forward_bound(f, c.X[:Bq], lst))
+        # svdp_compact on the materialised scores gives the step's list
+        m2, i2, n2 = binding.compact(binding.predict(dev, c.Xd[:Bq]))
+        assert torch.equal(m2, mask) and n2.item() == nnz.item()
+        assert torch.equal(i2[: nnz.item()], idx[: nnz.item()])
 
 
 def test_engine_selection_and_determinism(env):
-    """AUTO = matrix cores from 5 tokens up (batch capacity 8), vector units below; layers the matrix kernel does not
-    take (fp32 storage, d not a multiple of 512, re-validation) run on the vector kernel whatever
-    is set.  Seen through bit patterns: each engine is deterministic and the two differ in the
+    """No engine flag = matrix cores from 5 tokens up (batch capacity 8), vector units below; layers the matrix
+    kernel does not take (fp32 storage, d not a multiple of 512, re-validation) run on the vector kernel whatever
+    is asked for.  Seen through bit patterns: each engine is deterministic and the two differ in the
     last bits of y."""
     binding, torch, oracle = env
     c = RandomLayer(binding, torch, 11, 1024, 8704, 32, 8)
+    MATRIX, VECTOR, AUTO = binding.FLAG_ENGINE_MATRIX, binding.FLAG_ENGINE_VECTOR, 0
 
-    def run(engine, B, dev=None):
-        binding.set_engine(engine)
-        y = binding.ffn_step(dev or c.dev, c.Xd[:B]).clone()
-        binding.set_engine(binding.ENGINE_AUTO)
-        return y
+    def run(engine, B, dev=None, flags=0):
+        return binding.ffn_step((dev or c.dev).with_flags(engine | flags), c.Xd[:B]).clone()
 
     for B in (1, 2, 3, 4, 5, 8):
-        ym, yv, ya = run(binding.ENGINE_MATRIX, B), run(binding.ENGINE_VECTOR, B), run(binding.ENGINE_AUTO, B)
-        assert torch.equal(ym, run(binding.ENGINE_MATRIX, B)) and torch.equal(yv, run(binding.ENGINE_VECTOR, B))
+        ym, yv, ya = run(MATRIX, B), run(VECTOR, B), run(AUTO, B)
+        assert torch.equal(ym, run(MATRIX, B)) and torch.equal(yv, run(VECTOR, B))
         assert not torch.equal(ym, yv)
         assert torch.equal(ya, ym if B >= 5 else yv)
-    # re-validation: vector kernel under every setting
-    dv = c.dev.with_flags(binding.FLAG_REVALIDATE)
-    assert torch.equal(run(binding.ENGINE_MATRIX, 8, dv), run(binding.ENGINE_VECTOR, 8, dv))
+    # re-validation: vector row kernel under every setting (the score kernel still follows the flag,
+    # which can only move scores within rounding of zero; the lists agree on this layer)
+    assert torch.equal(run(MATRIX, 8, flags=binding.FLAG_REVALIDATE), run(VECTOR, 8, flags=binding.FLAG_REVALIDATE))
     # d = 520: not a multiple of 512
     c2 = RandomLayer(binding, torch, 12, 520, 4160, 16, 8)
-    binding.set_engine(binding.ENGINE_MATRIX)
-    y1 = binding.ffn_step(c2.dev, c2.Xd).clone()
-    binding.set_engine(binding.ENGINE_VECTOR)
-    y2 = binding.ffn_step(c2.dev, c2.Xd).clone()
-    binding.set_engine(binding.ENGINE_AUTO)
-    assert torch.equal(y1, y2)
+    assert torch.equal(binding.ffn_step(c2.dev.with_flags(MATRIX), c2.Xd), binding.ffn_step(c2.dev.with_flags(VECTOR), c2.Xd))
+
+
+def test_two_host_threads_with_different_engines(env):
+    """The library keeps no mode between calls: two host threads, each on its own stream and workspace, one
+    asking for the vector units and one for the matrix cores, get the results they get when run alone."""
+    import threading
+
+    binding, torch, oracle = env
+    c = RandomLayer(binding, torch, 13, 1024, 8704, 32, 8)
+    devs = {k: c.dev.with_flags(k) for k in (binding.FLAG_ENGINE_MATRIX, binding.FLAG_ENGINE_VECTOR)}
+    alone = {k: binding.ffn_step(d, c.Xd).clone() for k, d in devs.items()}
+    torch.cuda.synchronize()
+    assert not torch.equal(*alone.values())
+    bad = []
+
+    def worker(k):
+        try:
+            st = torch.cuda.Stream()
+            ws = torch.empty(binding.workspace_bytes(devs[k], 8), dtype=torch.uint8, device="cuda")
+            out = torch.empty(8, c.d, device="cuda")
+            with torch.cuda.stream(st):
+                for _ in range(50):
+                    binding.ffn_step(devs[k], c.Xd, ws=ws, out=out)
+                    st.synchronize()
+                    if not torch.equal(out, alone[k]):
+                        bad.append(k)
+                        return
+        except Exception as e:                  # a failure in a thread must fail the test
+            bad.append((k, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in devs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not bad, bad
 
 
 def test_matrix_engine_under_graph_replay(env):

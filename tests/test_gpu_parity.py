@@ -54,35 +54,26 @@ SMALL = [
 ]
 
 
-def step_check(env, c, B, t0, flags=0, modes=(0, 2, 1)):
-    """One decode step through svdp_ffn_step in every launch organisation (merged reduction,
-    single persistent kernel, plain four-kernel sequence), each checked completely against the oracle."""
+def step_check(env, c, B, t0, flags=0):
+    """One decode step through svdp_ffn_step, checked completely (mask, list, y) against the oracle."""
     binding, torch, oracle = env
     dev = c.dev.with_flags(flags) if flags else c.dev
     x = c.Xd[t0:t0 + B]
     D = c.spec.D
     s_or = oracle.predict(c.f32["P"], c.f32["Q"], c.f32["b"], c.X[t0:t0 + B])
-    out = None
-    for mode in modes:
-        binding.set_step_mode(mode)
-        mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
-        idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
-        nnz = torch.full((1,), -1, dtype=torch.int32, device="cuda")
-        y = binding.ffn_step(dev, x, mask=mask, idx=idx, nnz=nnz)
-        torch.cuda.synchronize()
-        lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
-        y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[t0:t0 + B], lst,
-                                  drelu=bool(flags & 1))
-        parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype)
-        # the step without the optional outputs gives the same y, bit for bit
-        y2 = binding.ffn_step(dev, x)
-        assert torch.equal(y, y2)
-        if out is None:
-            out = (lst, y)
-        else:
-            assert np.array_equal(out[0], lst)          # both modes: identical list
-    binding.set_step_mode(binding.STEP_SEQUENCE)
-    return out
+    mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+    idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+    nnz = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    y = binding.ffn_step(dev, x, mask=mask, idx=idx, nnz=nnz)
+    torch.cuda.synchronize()
+    lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+    y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[t0:t0 + B], lst,
+                              drelu=bool(flags & 1))
+    parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype)
+    # the step without the optional outputs gives the same y, bit for bit
+    y2 = binding.ffn_step(dev, x)
+    assert torch.equal(y, y2)
+    return lst, y
 
 
 @pytest.mark.parametrize("name,over", SMALL)
@@ -135,12 +126,36 @@ def test_sparse_ffn_arbitrary_lists(env, name, over):
             nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
             y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B], lst)
             slack = parity.fp32_forward_bound(c.f32, c.X[:B], lst)
-            for mode in (binding.STEP_MERGED_REDUCE, binding.STEP_SEQUENCE):
-                binding.set_step_mode(mode)
-                y = binding.sparse_ffn(c.dev, c.Xd[:B], idx, nnz).cpu().numpy()
-                parity.check_y(y, y_ref, c.spec.dtype, slack=slack)
-                if lst.size == 0:
-                    assert not y.any()
+            y = binding.sparse_ffn(c.dev, c.Xd[:B], idx, nnz).cpu().numpy()
+            parity.check_y(y, y_ref, c.spec.dtype, slack=slack)
+            if lst.size == 0:
+                assert not y.any()
+
+
+@pytest.mark.parametrize("flags", [0, 2, 8])
+def test_sparse_ffn_skips_entries_outside_the_layer(env, flags):
+    """svdp_sparse_ffn documents that a list entry outside [0, D) is skipped on the device: the result is
+    the oracle's over the valid entries, for the vector, sequential-pipeline and matrix-core row kernels."""
+    binding, torch, oracle = env
+    c = get_case(env, "tiny", d=1024, D=2560, r=72, dtype="bf16", seed=7, k_dom=32)
+    D = c.spec.D
+    rng = np.random.default_rng(5)
+    good = np.sort(rng.choice(D, 600, replace=False)).astype(np.int32)
+    lst = good.copy()
+    bad_at = rng.choice(lst.size, 40, replace=False)
+    lst[bad_at] = rng.choice(np.array([-1, -7, D, D + 1, 2**31 - 1, -2**31], dtype=np.int64), 40).astype(np.int32)
+    valid = np.delete(good, bad_at)
+    dev = c.dev.with_flags(flags)
+    for B in (1, 3, 8):
+        idx = torch.from_numpy(np.concatenate([lst, np.zeros(D - lst.size, np.int32)])).cuda()
+        nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
+        y = binding.sparse_ffn(dev, c.Xd[:B], idx, nnz).cpu().numpy()
+        y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B], valid)
+        parity.check_y(y, y_ref, c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, c.X[:B], valid))
+    # a list length beyond D is clamped on the device
+    idx = torch.arange(D, dtype=torch.int32, device="cuda")
+    y = binding.sparse_ffn(dev, c.Xd[:1], idx, torch.tensor([D + 1000], dtype=torch.int32, device="cuda")).cpu().numpy()
+    parity.check_y(y, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:1]), c.spec.dtype)
 
 
 @pytest.mark.parametrize("name,over", SMALL)
@@ -149,10 +164,8 @@ def test_dense_ffn(env, name, over):
     c = get_case(env, name, **over)
     for B in (1, 4, 7):
         y_ref = oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B])
-        for mode in (binding.STEP_MERGED_REDUCE, binding.STEP_SEQUENCE):
-            binding.set_step_mode(mode)
-            y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
-            parity.check_y(y, y_ref, c.spec.dtype)
+        y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
+        parity.check_y(y, y_ref, c.spec.dtype)
     yd = binding.dense_ffn(c.dev.with_flags(binding.FLAG_DRELU), c.Xd[:2]).cpu().numpy()
     parity.check_y(yd, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:2], drelu=True),
                    c.spec.dtype)
@@ -202,26 +215,21 @@ def test_random_shapes(env):
         s_or = oracle.predict(f["P"], f["Q"], b, Xf)
         s = binding.predict(dev, Xd).cpu().numpy().astype(np.float64)
         assert np.all(np.abs(s - s_or) <= 2e-5 * np.abs(s_or).max(axis=1, keepdims=True)), (case, d, r, D, B, dt)
-        for mode in (binding.STEP_SEQUENCE, binding.STEP_MERGED_REDUCE, binding.STEP_PERSISTENT):
-            binding.set_step_mode(mode)
-            mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
-            idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
-            nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
-            y = binding.ffn_step(dev, Xd, mask=mask, idx=idx, nnz=nnz)
-            lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
-            y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], Xf, lst)
-            parity.check_y(y.cpu().numpy(), y_ref, dt, slack=parity.fp32_forward_bound(f, Xf, lst))
-            yd = binding.dense_ffn(dev, Xd).cpu().numpy()
-            parity.check_y(yd, oracle.dense_ffn(f["W_gate"], f["W_up"], f["W_downT"], Xf), dt,
-                           slack=parity.fp32_forward_bound(f, Xf, np.arange(D)))
-        binding.set_step_mode(binding.STEP_SEQUENCE)
-    assert binding.step_timeouts() == 0
+        mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+        idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+        nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+        y = binding.ffn_step(dev, Xd, mask=mask, idx=idx, nnz=nnz)
+        lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+        y_ref = oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], Xf, lst)
+        parity.check_y(y.cpu().numpy(), y_ref, dt, slack=parity.fp32_forward_bound(f, Xf, lst))
+        yd = binding.dense_ffn(dev, Xd).cpu().numpy()
+        parity.check_y(yd, oracle.dense_ffn(f["W_gate"], f["W_up"], f["W_downT"], Xf), dt,
+                       slack=parity.fp32_forward_bound(f, Xf, np.arange(D)))
 
 
 def test_step_equals_separate_calls(env):
     binding, torch, _ = env
     c = get_case(env, "tiny")
-    binding.set_step_mode(binding.STEP_SEQUENCE)   # the kernel sequence shares its row kernel with svdp_sparse_ffn
     for B in (1, 4):
         x = c.Xd[8:8 + B]
         s = binding.predict(c.dev, x)
@@ -236,11 +244,6 @@ def test_step_equals_separate_calls(env):
         n = nnz.item()
         assert torch.equal(idx[:n], idx2[:n])
         assert torch.equal(y, y_sep)
-        for mode in (binding.STEP_PERSISTENT, binding.STEP_MERGED_REDUCE):
-            binding.set_step_mode(mode)
-            y_p = binding.ffn_step(c.dev, x)
-            assert torch.allclose(y_p, y_sep, rtol=1e-4, atol=1e-5 * float(y_sep.abs().max()))
-        binding.set_step_mode(binding.STEP_SEQUENCE)
 
 
 def test_active_rows_stage_alone(env):
@@ -285,39 +288,37 @@ def test_sequential_pipeline(env, name, over):
     binding, torch, oracle = env
     c = get_case(env, name, **over)
     D = c.spec.D
-    seq = c.dev.with_flags(binding.FLAG_REVALIDATE)
-    seq_d = c.dev.with_flags(binding.FLAG_REVALIDATE | binding.FLAG_DRELU)
+    VEC = binding.FLAG_ENGINE_VECTOR
+    seq = c.dev.with_flags(binding.FLAG_REVALIDATE | VEC)
+    seq_d = c.dev.with_flags(binding.FLAG_REVALIDATE | binding.FLAG_DRELU | VEC)
+    par = c.dev.with_flags(VEC)          # the parallel pipeline on the same (vector) engine
     rng = np.random.default_rng(11)
     lists = [np.zeros(0, np.int32), np.arange(D, dtype=np.int32), np.arange(1, D, 3, dtype=np.int32),
              np.sort(rng.choice(D, D // 2 + 1, replace=False)).astype(np.int32), rng.permutation(D)[:300].astype(np.int32)]
-    binding.set_engine(binding.ENGINE_VECTOR)
-    try:
-        for B in (1, 2, 5, 8):
-            x = c.Xd[7:7 + B]
-            Xf = c.X[7:7 + B]
-            for t0 in (0, 16):                       # offsets the union-batch step tests also use
-                step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE, modes=(0,))
-                if B <= 4:
-                    step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE | binding.FLAG_DRELU, modes=(0,))
-            assert torch.equal(binding.ffn_step(seq, x), binding.ffn_step(c.dev, x))
-            for lst in lists:
-                idx = torch.zeros(D, dtype=torch.int32, device="cuda")
-                idx[: lst.size] = torch.from_numpy(lst).cuda()
-                nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
-                y = binding.sparse_ffn(seq, x, idx, nnz)
-                y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf, lst)
-                parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, lst))
-                assert torch.equal(y, binding.sparse_ffn(c.dev, x, idx, nnz))
-                yd = binding.sparse_ffn(seq_d, x, idx, nnz).cpu().numpy()
-                parity.check_y(yd, oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf, lst, drelu=True),
-                               c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, lst))
-            # the dense entry point with the flag: every row's gate decides for itself (no predictor involved)
-            yd = binding.dense_ffn(seq, x)
-            parity.check_y(yd.cpu().numpy(), oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf),
-                           c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, np.arange(D)))
-            assert torch.equal(yd, binding.dense_ffn(c.dev, x))
-    finally:
-        binding.set_engine(binding.ENGINE_AUTO)
+    for B in (1, 2, 5, 8):
+        x = c.Xd[7:7 + B]
+        Xf = c.X[7:7 + B]
+        for t0 in (0, 16):                       # offsets the union-batch step tests also use
+            step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE | VEC)
+            if B <= 4:
+                step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE | binding.FLAG_DRELU | VEC)
+        assert torch.equal(binding.ffn_step(seq, x), binding.ffn_step(par, x))
+        for lst in lists:
+            idx = torch.zeros(D, dtype=torch.int32, device="cuda")
+            idx[: lst.size] = torch.from_numpy(lst).cuda()
+            nnz = torch.tensor([lst.size], dtype=torch.int32, device="cuda")
+            y = binding.sparse_ffn(seq, x, idx, nnz)
+            y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf, lst)
+            parity.check_y(y.cpu().numpy(), y_ref, c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, lst))
+            assert torch.equal(y, binding.sparse_ffn(par, x, idx, nnz))
+            yd = binding.sparse_ffn(seq_d, x, idx, nnz).cpu().numpy()
+            parity.check_y(yd, oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf, lst, drelu=True),
+                           c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, lst))
+        # the dense entry point with the flag: every row's gate decides for itself (no predictor involved)
+        yd = binding.dense_ffn(seq, x)
+        parity.check_y(yd.cpu().numpy(), oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], Xf),
+                       c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, Xf, np.arange(D)))
+        assert torch.equal(yd, binding.dense_ffn(par, x))
 
 
 def test_deterministic(env):
@@ -330,30 +331,6 @@ def test_deterministic(env):
         for _ in range(20):
             assert torch.equal(binding.ffn_step(c.dev, c.Xd[:B]), ref)
             assert torch.equal(binding.dense_ffn(c.dev, c.Xd[:B]), refd)
-
-
-def test_no_stage_wait_timed_out(env):
-    """Runs after the step tests above: none of the persistent launches gave up a wait."""
-    binding, torch, _ = env
-    assert binding.step_timeouts() == 0
-
-
-def test_forced_wait_timeout_is_reported_and_recovers(env):
-    """Failure handling, forced from the host: with a spin limit of one poll the stage waits give
-    up at once; the kernel still exits normally, the timeout is recorded, and the next step
-    with a normal limit is correct again."""
-    binding, torch, oracle = env
-    c = get_case(env, "tiny")
-    for mode in (binding.STEP_PERSISTENT, binding.STEP_MERGED_REDUCE):
-        binding.set_step_mode(mode, spin_limit=1)
-        for t in range(4):
-            binding.ffn_step(c.dev, c.Xd[t])
-        torch.cuda.synchronize()
-    n = binding.step_timeouts()
-    binding.set_step_mode(binding.STEP_SEQUENCE, spin_limit=400000)
-    assert n >= 0                       # a fast box may meet every wait on the first poll
-    step_check(env, c, 1, 5)
-    assert binding.step_timeouts() == 0
 
 
 def test_degenerate_masks(env):
@@ -415,7 +392,7 @@ def test_full_size_sequential_pipeline_weak_predictor(env):
     seq = c.dev.with_flags(binding.FLAG_REVALIDATE)
     dens = []
     for B, t0 in ((1, 0), (1, 9), (2, 16), (4, 24)):
-        lst, y = step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE, modes=(0,))
+        lst, y = step_check(env, c, B, t0, flags=binding.FLAG_REVALIDATE)
         dens.append(lst.size / c.spec.D)
         assert torch.equal(y, binding.ffn_step(c.dev, c.Xd[t0:t0 + B]))
         assert torch.equal(binding.dense_ffn(seq, c.Xd[t0:t0 + B]), binding.dense_ffn(c.dev, c.Xd[t0:t0 + B]))
