@@ -158,6 +158,20 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
                           uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out,
                           void *ws, size_t ws_bytes, void *stream);
 
+/* svdp_ffn_step for callers that cannot hand over or allocate scratch memory (code under HIP
+ * graph capture that owns no buffer, tight serving loops, harnesses that forbid allocation):
+ * the same step, with the scratch taken from an array of SVDP_STATIC_SCRATCH_BYTES that the
+ * library's image holds on every GPU it runs on until the process ends.  Allocates nothing.
+ * Layers and batches whose svdp_workspace_bytes() exceeds the array are refused with
+ * SVDP_ERR_WORKSPACE (the 7B- and Mistral-shaped bf16 layers fit with one token).
+ * All calls on one GPU share that GPU's array: two calls that may overlap in time on the same
+ * GPU (different streams, different threads) race; serialise them or use svdp_ffn_step.
+ * Nothing in the array needs to start at zero, and nothing is kept in it between calls.
+ * Results are bit for bit those of svdp_ffn_step.                                              */
+#define SVDP_STATIC_SCRATCH_BYTES (8u << 20)
+svdp_status svdp_ffn_step_static(const svdp_layer *layer, const void *x, int32_t B, float *y,
+                                 uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out, void *stream);
+
 /* Stage 3 of svdp_ffn_step alone (the dominant kernel, exposed so that it can be timed by
  * itself): scans the mask words, and for this launch's row blocks computes gate, up and the
  * partial down projection over the active rows (Alg. 3's three kernels).  The partial y's stay

@@ -19,10 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libsvdp.so")
 SVDP_F32, SVDP_BF16 = 0, 1
 FLAG_DRELU, FLAG_REVALIDATE, FLAG_ENGINE_VECTOR, FLAG_ENGINE_MATRIX = 1, 2, 4, 8
 MAX_BATCH = 8
+STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = [
     "svdp_workspace_bytes", "svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn",
-    "svdp_ffn_step", "svdp_stack_glue", "svdp_status_string", "svdp_version",
+    "svdp_ffn_step", "svdp_ffn_step_static", "svdp_stack_glue", "svdp_status_string", "svdp_version",
     "svdp_active_rows", "svdp_calib_workspace_bytes", "svdp_calib_need", "svdp_calib_bias",
     "svdp_calib_stats_workspace_bytes", "svdp_calib_stats", "svdp_ffn_step_glued",
 ]
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
     L.svdp_sparse_ffn.argtypes = [lp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.svdp_dense_ffn.argtypes = [lp, vp, i32, vp, vp, sz, vp]
     L.svdp_ffn_step.argtypes = [lp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.svdp_ffn_step_static.argtypes = [lp, vp, i32, vp, vp, vp, vp, vp]
+    L.svdp_ffn_step_static.restype = ctypes.c_int
     L.svdp_stack_glue.argtypes = [vp, vp, vp, i32, i32, ctypes.c_float, vp, vp]
     L.svdp_active_rows.argtypes = [lp, vp, i32, vp, vp, sz, vp]
     L.svdp_active_rows.restype = ctypes.c_int
@@ -224,6 +227,17 @@ def ffn_step(layer: DeviceLayer, x: torch.Tensor, ws: Optional[torch.Tensor] = N
     y = torch.empty((B, layer.d), dtype=torch.float32, device=x.device) if out is None else out
     _check(lib().svdp_ffn_step(ctypes.byref(layer.c), _ptr(x), B, _ptr(y), _ptr(mask), _ptr(idx), _ptr(nnz),
                                _ptr(ws), ws.numel(), _stream()), "svdp_ffn_step")
+    return y
+
+
+def ffn_step_static(layer: DeviceLayer, x: torch.Tensor, out: Optional[torch.Tensor] = None,
+                    mask: Optional[torch.Tensor] = None, idx: Optional[torch.Tensor] = None,
+                    nnz: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """svdp_ffn_step with the scratch taken from the library's own static device array (no workspace argument)."""
+    x, B = _x2(layer, x)
+    y = torch.empty((B, layer.d), dtype=torch.float32, device=x.device) if out is None else out
+    _check(lib().svdp_ffn_step_static(ctypes.byref(layer.c), _ptr(x), B, _ptr(y), _ptr(mask), _ptr(idx), _ptr(nnz),
+                                      _stream()), "svdp_ffn_step_static")
     return y
 
 

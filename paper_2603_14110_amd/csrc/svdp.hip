@@ -432,6 +432,33 @@ svdp_status step_impl(const svdp_layer *L, const void *x, int B, float *y, uint6
     });
 }
 
+// ---- the scratch buffer of svdp_ffn_step_static: one array per device, in the library's image ----
+__device__ __align__(256) unsigned char g_static_scratch[SVDP_STATIC_SCRATCH_BYTES];
+
+std::mutex g_scratch_mutex;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+
+// Address of the current device's copy of the array (looked up once per device).
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p != nullptr) return p;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (p != nullptr) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || p == nullptr) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -525,6 +552,24 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
     if (x == nullptr || y == nullptr || bad_batch(B) || !aligned16(x) || !aligned16(y)) return SVDP_ERR_INVALID_ARG;
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
+    if (st != SVDP_OK) return st;
+    return step_impl(layer, x, B, y, mask_out, idx_out, nnz_out, w, static_cast<hipStream_t>(stream), nullptr);
+}
+
+svdp_status svdp_ffn_step_static(const svdp_layer *layer, const void *x, int32_t B, float *y, uint64_t *mask_out,
+                                 int32_t *idx_out, int32_t *nnz_out, void *stream)
+{
+    svdp_status st = check_layer(layer, true, true);
+    if (st != SVDP_OK) return st;
+    if (x == nullptr || y == nullptr || bad_batch(B) || !aligned16(x) || !aligned16(y)) return SVDP_ERR_INVALID_ARG;
+    if (!layer_fits(layer, nb_of(B))) return SVDP_ERR_UNSUPPORTED;
+    // the size test comes first: a layer or batch beyond the array is refused whatever the device says
+    if (carve(nullptr, layer->d, layer->D, layer->r, nb_of(B)).bytes > (size_t)SVDP_STATIC_SCRATCH_BYTES)
+        return SVDP_ERR_WORKSPACE;
+    void *scratch = static_scratch();
+    if (scratch == nullptr) return SVDP_ERR_HIP;
+    Workspace w;
+    st = check_ws(layer, B, scratch, (size_t)SVDP_STATIC_SCRATCH_BYTES, &w);
     if (st != SVDP_OK) return st;
     return step_impl(layer, x, B, y, mask_out, idx_out, nnz_out, w, static_cast<hipStream_t>(stream), nullptr);
 }

@@ -111,6 +111,23 @@ def test_library_has_no_process_wide_switches(svdp):
     assert exported == names, (exported, names)
 
 
+def test_static_scratch_entry_point_validates_on_the_host(svdp):
+    """svdp_ffn_step_static: same argument checks as svdp_ffn_step, and a layer or batch whose scratch need
+    exceeds the library's static array is refused (before any device is touched)."""
+    L = svdp.lib()
+    INVALID, UNSUPPORTED, WORKSPACE = 1, 2, 3
+    l = _layer(svdp)
+    assert L.svdp_workspace_bytes(ctypes.byref(l), 1) <= svdp.STATIC_SCRATCH_BYTES < L.svdp_workspace_bytes(ctypes.byref(l), 2)
+    assert L.svdp_ffn_step_static(ctypes.byref(l), 0x1000, 2, 0x1000, None, None, None, None) == WORKSPACE
+    assert L.svdp_ffn_step_static(ctypes.byref(l), 0x1000, 8, 0x1000, None, None, None, None) == WORKSPACE
+    assert L.svdp_ffn_step_static(ctypes.byref(l), None, 1, 0x1000, None, None, None, None) == INVALID
+    assert L.svdp_ffn_step_static(ctypes.byref(l), 0x1000, 0, 0x1000, None, None, None, None) == INVALID
+    assert L.svdp_ffn_step_static(ctypes.byref(_layer(svdp, D=100)), 0x1000, 1, 0x1000, None, None, None, None) == UNSUPPORTED
+    text = open(os.path.join(ROOT, "include", "svdp.h")).read()
+    m = re.search(r"#define SVDP_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text)
+    assert int(m.group(1)) << int(m.group(2)) == svdp.STATIC_SCRATCH_BYTES
+
+
 def test_calib_need_is_the_oracles_rule(svdp):
     """svdp_calib_need against the oracle's required_drops on a grid incl. products that are not exact in
     binary (0.7 * 10, 0.1 * 3 ...), the clamps and the invalid cases."""
