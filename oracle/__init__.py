@@ -49,6 +49,12 @@ def _load():
     return _lib
 
 
+def set_threads(n: int) -> None:
+    """Number of OpenMP threads the C oracle uses from now on (timing only; the results do not depend on it)."""
+    _load()
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
 def _f32(a, shape=None) -> np.ndarray:
     a = np.ascontiguousarray(a, dtype=np.float32)
     if shape is not None:

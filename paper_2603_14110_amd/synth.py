@@ -99,6 +99,8 @@ def workload(name: str, **over) -> LayerSpec:
         "13b": LayerSpec("13b", 5120, 13824, 320, BF16, 64, 0.92, 1024, seed=2000),
         # Mistral-7B-shaped layer (d=4096, D=14336)
         "mistral": LayerSpec("mistral", 4096, 14336, 256, BF16, 64, 0.90, 1024, seed=3000),
+        # SparseQwen2-7B-shaped layer (d=3584, D=18944), the paper's rank for it
+        "qwen": LayerSpec("qwen", 3584, 18944, 512, BF16, 64, 0.90, 1024, seed=5000),
     }
     spec = table[name]
     if over:

@@ -33,6 +33,47 @@ def test_every_declared_symbol_is_exported(svdp):
         assert getattr(L, n) is not None
 
 
+def test_probe_library_exports_what_its_header_declares():
+    """libsvdp_probe (the benchmark's measurement helpers): loads, and exports exactly the header's symbols."""
+    import subprocess
+
+    from paper_2603_14110_amd import build, probe
+
+    if not os.path.exists(probe.LIB_PATH):
+        build.build_probe()
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "svdp_probe.h")).read(), flags=re.S)
+    declared = sorted(set(re.findall(r"\b(svdp_probe_[a-z_]+)\s*\(", text)))
+    assert declared == sorted(probe.EXPORTS)
+    L = probe.lib()
+    for n in declared:
+        assert getattr(L, n) is not None
+    out = subprocess.run(["nm", "-D", "--defined-only", probe.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    assert sorted(set(re.findall(r"\b(svdp_probe_[a-z_0-9]+)\b", out))) == declared
+    # host-side validation: nothing is launched for bad arguments
+    assert L.svdp_probe_null(0, 64, None) == 1 and L.svdp_probe_null(1, 2048, None) == 1
+    assert L.svdp_probe_stamp(None, None) == 1 and L.svdp_probe_handover(None, None) == 1
+    assert L.svdp_probe_stream_read(0x1000, 24, 4, 0x1000, None) == 1          # not a multiple of 16 bytes
+    assert L.svdp_probe_chase(None, 4, 4, 0x1000, None) == 1
+
+
+def test_bench_sample_is_stratified_and_seeded():
+    """The timed subsample of bench.py: fixed for a given K, without repeats, and its mean density follows the
+    stream's within half a percentage point from 20 steps up, on a skewed density distribution."""
+    import numpy as np
+
+    import bench
+
+    rng = np.random.default_rng(5)
+    dens = np.clip(rng.gamma(0.45, 0.22, 1024), 0.0, 0.9)          # median well under the mean, a long tail
+    for K in (5, 20, 64, 200, 1024, 2000):
+        s1, s2 = bench.stratified_sample(np, dens, K), bench.stratified_sample(np, dens, K)
+        assert np.array_equal(s1, s2) and len(set(s1.tolist())) == min(K, 1024) == len(s1)
+        if K >= 20:
+            assert abs(dens[s1].mean() - dens.mean()) < 0.005
+    first20 = dens[:20].mean()
+    assert abs(dens[bench.stratified_sample(np, dens, 20)].mean() - dens.mean()) <= abs(first20 - dens.mean()) + 0.005
+
+
 def test_status_strings_and_version(svdp):
     L = svdp.lib()
     seen = {L.svdp_status_string(i).decode() for i in range(5)}

@@ -367,20 +367,46 @@ def test_stack_glue(env):
 # ---- full-size layers, in the launch configuration the benchmark times ----------------
 
 
-FULL = [("7b", {}, 1), ("7b", dict(r=128), 1), ("7b", dict(r=512), 1), ("13b", {}, 1),
-        ("mistral", {}, 1), ("mistral", {}, 2), ("mistral", {}, 4), ("mistral", {}, 8)]
+# (workload, overrides, batch, first tokens of the steps checked)
+FULL = [("7b", {}, 1, (0, 8, 16, 24)), ("7b", dict(r=128), 1, (0, 8, 16, 24)), ("7b", dict(r=512), 1, (0, 8, 16, 24)),
+        ("13b", {}, 1, (0, 8, 16, 24)),
+        ("mistral", {}, 1, (0, 8, 16, 24)), ("mistral", {}, 2, (0, 8, 16, 24)), ("mistral", {}, 4, (0, 8, 16, 24)),
+        ("mistral", {}, 8, (0, 8, 16, 24)),
+        # batch sizes that leave token slots of the 4- and 8-token kernels idle
+        ("mistral", {}, 3, (32,)), ("mistral", {}, 5, (40,)), ("mistral", {}, 6, (48,)), ("mistral", {}, 7, (56,)),
+        # the third shape of the paper's model table (App. D): D > 16384, so a lane of the row kernel's mask scan
+        # owns more mask words than it keeps in registers; d is not a multiple of 4096 (ragged row batches)
+        ("qwen", {}, 1, (0, 8, 16)), ("qwen", {}, 8, (0, 24))]
 
 
-@pytest.mark.parametrize("name,over,B", FULL)
-def test_full_size_sampled_tokens(env, name, over, B):
+@pytest.mark.parametrize("name,over,B,offsets", FULL)
+def test_full_size_sampled_tokens(env, name, over, B, offsets):
     """Full shapes; a sample of decode steps checked completely (mask, list, y) against the
     oracle, plus the dense baseline on one batch."""
     binding, torch, oracle = env
     c = get_case(env, name, n_tok=64, **over)
-    for t0 in (0, 8, 16, 24):
+    for t0 in offsets:
         step_check(env, c, B, t0)
     y = binding.dense_ffn(c.dev, c.Xd[:B]).cpu().numpy()
     parity.check_y(y, oracle.dense_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:B]), c.spec.dtype)
+
+
+def test_full_size_fixed_sparsity_lists_qwen_shape(env):
+    """The executor-table protocol as `bench.py --table4` runs it on the largest shape (d=3584, D=18944): random
+    ascending lists at 50 % and 95 % sparsity through svdp_sparse_ffn, against the oracle."""
+    binding, torch, oracle = env
+    c = get_case(env, "qwen", n_tok=64)
+    D = c.spec.D
+    rng = np.random.default_rng(7)
+    for sp in (0.50, 0.95):
+        n = int(round((1.0 - sp) * D))
+        lst = np.sort(rng.choice(D, n, replace=False)).astype(np.int32)
+        idx = torch.zeros(D, dtype=torch.int32, device="cuda")
+        idx[:n] = torch.from_numpy(lst).cuda()
+        nnz = torch.tensor([n], dtype=torch.int32, device="cuda")
+        y = binding.sparse_ffn(c.dev, c.Xd[:1], idx, nnz).cpu().numpy()
+        y_ref = oracle.sparse_ffn(c.f32["W_gate"], c.f32["W_up"], c.f32["W_downT"], c.X[:1], lst)
+        parity.check_y(y, y_ref, c.spec.dtype, slack=parity.fp32_forward_bound(c.f32, c.X[:1], lst))
 
 
 def test_full_size_sequential_pipeline_weak_predictor(env):

@@ -148,3 +148,57 @@ def test_glued_step_fp32(oracle):
     assert torch.equal(x_out[0], binding.stack_glue(torch.from_numpy(xp).cuda(), torch.from_numpy(yp).cuda(),
                                                     torch.from_numpy(shift).cuda()))
     assert torch.equal(y, binding.ffn_step(dev, x_out))
+
+
+def test_real_stack_specs_teacher_forced(oracle):
+    """Three layers of the 32-layer benchmark stack at full size (the lowest, a middle and the highest of the
+    per-layer target sparsities drawn from U(0.80, 0.95)), each fed what the stack feeds it: the glue of a previous
+    token and output, re-centred on the layer's own direction.  Teacher-forced: the oracle's glue output goes into
+    svdp_ffn_step; svdp_ffn_step_glued forms the token itself and is checked against the oracle on the token it
+    formed (one bf16 rounding apart from the oracle's)."""
+    import torch
+    from paper_2603_14110_amd import binding, stack
+
+    binding.lib()
+    specs = sorted(stack.stack_specs(32), key=lambda sp: sp.sparsity)
+    rng = np.random.default_rng(41)
+    for sp in (specs[0], specs[len(specs) // 2], specs[-1]):
+        L = synth.load_or_make(sp)
+        f = {k: L.f32(k) for k in ("W_gate", "W_up", "W_downT", "P", "Q", "b")}
+        dev = binding.DeviceLayer.from_synth(L)
+        d, D = sp.d, sp.D
+        shift = (2.0 * L.u).astype(np.float32)
+        dens = []
+        for t in range(3):
+            # previous layer's token and output: a token of the stream and an output of the FFN's typical size
+            xp_st = synth.to_storage(2.0 * rng.standard_normal(d) / np.sqrt(d) + rng.standard_normal(d), "bf16")
+            xp = synth.storage_to_f32(xp_st, "bf16")
+            yp = (rng.standard_normal(d) * 0.8).astype(np.float32)
+            x_or = oracle.stack_glue(xp.astype(np.float64), yp, shift)
+            x_st = synth.to_storage(x_or, "bf16")
+            x = synth.storage_to_f32(x_st, "bf16")
+            # (a) the plain step on the oracle's token
+            mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+            idx = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+            nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
+            y = binding.ffn_step(dev, binding.to_device(x_st, "bf16"), mask=mask, idx=idx, nnz=nnz)
+            s_or = oracle.predict(f["P"], f["Q"], f["b"], x[None])
+            lst = parity.check_mask_and_idx(s_or, mask.cpu().numpy(), idx.cpu().numpy(), nnz.item(), D)
+            parity.check_y(y.cpu().numpy(), oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], x[None], lst), "bf16")
+            dens.append(lst.size / D)
+            # (b) glue and step in the same launches
+            x_out = torch.zeros(1, d, dtype=torch.bfloat16, device="cuda")
+            mask2 = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+            idx2 = torch.full((D,), -1, dtype=torch.int32, device="cuda")
+            nnz2 = torch.zeros(1, dtype=torch.int32, device="cuda")
+            y2 = binding.ffn_step_glued(dev, binding.to_device(xp_st, "bf16")[None], torch.from_numpy(yp).cuda()[None],
+                                        torch.from_numpy(shift).cuda(), x_out, mask=mask2, idx=idx2, nnz=nnz2)
+            xg = x_out.float().cpu().numpy()[0]
+            assert np.all(np.abs(xg - x_or) <= 2.0 ** -8 * np.maximum(np.abs(x_or), 1.0))
+            s2 = oracle.predict(f["P"], f["Q"], f["b"], xg[None])
+            lst2 = parity.check_mask_and_idx(s2, mask2.cpu().numpy(), idx2.cpu().numpy(), nnz2.item(), D)
+            parity.check_y(y2.cpu().numpy(), oracle.sparse_ffn(f["W_gate"], f["W_up"], f["W_downT"], xg[None], lst2), "bf16")
+        # the realised density follows the layer's target (80 % to 95 % sparsity), loosely: three tokens
+        assert 0.0 < np.mean(dens) < 0.6, (sp.sparsity, dens)
+        del dev
+        torch.cuda.empty_cache()
