@@ -249,10 +249,14 @@ def run_layer(a, torch, np, binding, cost, synth):
     Y = torch.zeros((K, B, spec.d), dtype=torch.float32, device="cuda")
     NNZ = torch.zeros((K, 1), dtype=torch.int32, device="cuda")
     MASK = torch.zeros((K, spec.D // 64), dtype=torch.int64, device="cuda")
-    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    # untimed, before every timed replay: 1 GiB of other data is READ through the caches, so that nothing of the
+    # layer stays in them and they hold no dirty lines whose write-back would ride on the timed steps
+    probe.lib()
+    flush_buf = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+    flush_sink = torch.zeros(1, dtype=torch.int32, device="cuda")
 
-    def flush():                # untimed, before every timed replay: nothing of the layer stays in the caches
-        flush_buf.fill_(7)
+    def flush():
+        probe.stream_read(flush_buf, 1 << 30, 2048, flush_sink)
 
     def sparse_step(k):
         binding.ffn_step(copies[k % len(copies)], Xd[k], ws=ws, out=Y[k], nnz=NNZ[k], mask=MASK[k])
@@ -261,7 +265,7 @@ def run_layer(a, torch, np, binding, cost, synth):
         binding.ffn_step(base, Xd[k], ws=ws, out=Y[k])
 
     def rows_only(k):          # the dominant kernel by itself, on the mask words the steps produced
-        binding.active_rows(copies[k % len(copies)], Xd[k], MASK[k], ws=ws)
+        binding.active_rows(copies[k % len(copies)], Xd[k], MASK[k], ws=ws, first_kernel_only=True)
 
     engine_bits = a.flags & (binding.FLAG_ENGINE_VECTOR | binding.FLAG_ENGINE_MATRIX)
     plain = [c.with_flags(engine_bits) for c in copies]     # the dense baseline never takes the pipeline flags
@@ -289,7 +293,6 @@ def run_layer(a, torch, np, binding, cost, synth):
     # ---- each step's own duration: time stamps between the steps of a second graph
     per_step = None
     if graph:
-        probe.lib()
         stamps = torch.zeros(K + 1, dtype=torch.int64, device="cuda")
         pair = torch.zeros(257, dtype=torch.int64, device="cuda")
 
@@ -446,11 +449,12 @@ def traffic_pass(a, torch, np, binding, cost, synth):
     Xd = Xpool[torch.from_numpy(sel).cuda()].contiguous()
     NNZ = torch.zeros((K, 1), dtype=torch.int32, device="cuda")
     MASK = torch.zeros((K, spec.D // 64), dtype=torch.int64, device="cuda")
-    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    flush_buf = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+    flush_sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     torch.cuda.synchronize()
 
     def region(marker_blocks, fn, n):
-        flush_buf.fill_(7)
+        probe.stream_read(flush_buf, 1 << 30, 2048, flush_sink)
         probe.null(marker_blocks, 64)
         for k in range(n):
             fn(k)
@@ -458,7 +462,7 @@ def traffic_pass(a, torch, np, binding, cost, synth):
         torch.cuda.synchronize()
 
     region(7, lambda k: binding.ffn_step(copies[k % len(copies)], Xd[k], ws=ws, out=y, nnz=NNZ[k], mask=MASK[k]), K)
-    region(11, lambda k: binding.active_rows(copies[k % len(copies)], Xd[k], MASK[k], ws=ws), K)
+    region(11, lambda k: binding.active_rows(copies[k % len(copies)], Xd[k], MASK[k], ws=ws, first_kernel_only=True), K)
     Kd = min(K, 16)
     region(13, lambda k: binding.dense_ffn(copies[k % len(copies)], Xd[k], ws=ws, out=y), Kd)
     src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")

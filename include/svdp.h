@@ -172,13 +172,15 @@ svdp_status svdp_ffn_step(const svdp_layer *layer, const void *x, int32_t B, flo
 svdp_status svdp_ffn_step_static(const svdp_layer *layer, const void *x, int32_t B, float *y,
                                  uint64_t *mask_out, int32_t *idx_out, int32_t *nnz_out, void *stream);
 
-/* Stage 3 of svdp_ffn_step alone (the dominant kernel, exposed so that it can be timed by
- * itself): scans the mask words, and for this launch's row blocks computes gate, up and the
- * partial down projection over the active rows (Alg. 3's three kernels).  The partial y's stay
- * in the workspace; no y is produced.  mask: device [D/64] words as written by svdp_compact
- * or svdp_ffn_step.                                                                          */
+/* The sparse FFN of svdp_ffn_step from given mask words, without the predictor (Alg. 3 after its
+ * first line): the row kernel scans the mask words, takes its share of the ascending list and
+ * computes gate and up over the active rows; the down projection follows and y [B][d] is fully
+ * written, bit for bit what svdp_ffn_step gives for the same mask.  With y == NULL only the row
+ * kernel (the dominant one) is enqueued and its partial results stay in the workspace: that form
+ * exists so that the kernel can be timed by itself.  mask: device [D/64] words as written by svdp_compact or
+ * svdp_ffn_step.                                                                                  */
 svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask,
-                             void *ws, size_t ws_bytes, void *stream);
+                             float *y, void *ws, size_t ws_bytes, void *stream);
 
 /* Glue between stacked layers used by the stacked benchmark (not from the
  * paper): v = x + y; x_next = v / sqrt(mean(v^2) + eps) + shift, rounded to

@@ -65,7 +65,7 @@ def lib() -> ctypes.CDLL:
     L.svdp_ffn_step_static.argtypes = [lp, vp, i32, vp, vp, vp, vp, vp]
     L.svdp_ffn_step_static.restype = ctypes.c_int
     L.svdp_stack_glue.argtypes = [vp, vp, vp, i32, i32, ctypes.c_float, vp, vp]
-    L.svdp_active_rows.argtypes = [lp, vp, i32, vp, vp, sz, vp]
+    L.svdp_active_rows.argtypes = [lp, vp, i32, vp, vp, vp, sz, vp]
     L.svdp_active_rows.restype = ctypes.c_int
     for n in ("svdp_predict", "svdp_compact", "svdp_sparse_ffn", "svdp_dense_ffn", "svdp_ffn_step",
               "svdp_stack_glue"):
@@ -257,12 +257,18 @@ def ffn_step_glued(layer: DeviceLayer, x_prev: torch.Tensor, y_prev: torch.Tenso
     return y
 
 
-def active_rows(layer: DeviceLayer, x: torch.Tensor, mask: torch.Tensor, ws: Optional[torch.Tensor] = None) -> None:
-    """Stage 3 of the step alone (partial y's stay in the workspace); for timing the dominant kernel."""
+def active_rows(layer: DeviceLayer, x: torch.Tensor, mask: torch.Tensor, ws: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None, first_kernel_only: bool = False) -> Optional[torch.Tensor]:
+    """The sparse FFN from given mask words (no predictor).  With first_kernel_only the dominant kernel is
+    enqueued alone (its results stay in the workspace, nothing is returned): for timing it by itself."""
     x, B = _x2(layer, x)
     ws = layer.workspace(B) if ws is None else ws
-    _check(lib().svdp_active_rows(ctypes.byref(layer.c), _ptr(x), B, _ptr(mask), _ptr(ws), ws.numel(), _stream()),
-           "svdp_active_rows")
+    y = None
+    if not first_kernel_only:
+        y = torch.empty((B, layer.d), dtype=torch.float32, device=x.device) if out is None else out
+    _check(lib().svdp_active_rows(ctypes.byref(layer.c), _ptr(x), B, _ptr(mask), _ptr(y), _ptr(ws), ws.numel(),
+                                  _stream()), "svdp_active_rows")
+    return y
 
 
 def stack_glue(x: torch.Tensor, y: torch.Tensor, shift: torch.Tensor, eps: float = 1e-6,

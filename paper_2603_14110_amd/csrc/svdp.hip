@@ -590,12 +590,13 @@ svdp_status svdp_ffn_step_glued(const svdp_layer *layer, const void *x_prev, con
     return step_impl(layer, x_prev, B, y, mask_out, idx_out, nnz_out, w, static_cast<hipStream_t>(stream), &glue);
 }
 
-svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask, void *ws,
-                             size_t ws_bytes, void *stream)
+svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask, float *y,
+                             void *ws, size_t ws_bytes, void *stream)
 {
     svdp_status st = check_layer(layer, false, true);
     if (st != SVDP_OK) return st;
-    if (x == nullptr || mask == nullptr || bad_batch(B) || !aligned16(x)) return SVDP_ERR_INVALID_ARG;
+    if (x == nullptr || mask == nullptr || bad_batch(B) || !aligned16(x) || (y != nullptr && !aligned16(y)))
+        return SVDP_ERR_INVALID_ARG;
     Workspace w;
     st = check_ws(layer, B, ws, ws_bytes, &w);
     if (st != SVDP_OK) return st;
@@ -603,8 +604,10 @@ svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, 
         using W = typename decltype(wt)::type;
         constexpr int NB = decltype(nb)::value;
         if (!prepare_rows<W, NB, ROWS_MASK>(layer)) return SVDP_ERR_UNSUPPORTED;
-        return launch_rows_only<W, NB, ROWS_MASK>(layer, x, B, mask, nullptr, nullptr, nullptr, nullptr, w,
-                                                  static_cast<hipStream_t>(stream));
+        hipStream_t hs = static_cast<hipStream_t>(stream);
+        if (y == nullptr)
+            return launch_rows_only<W, NB, ROWS_MASK>(layer, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, hs);
+        return launch_rows<W, NB, ROWS_MASK>(layer, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, y, hs);
     });
 }
 

@@ -136,8 +136,9 @@ def test_validation_rejects_before_any_launch(svdp):
     assert L.svdp_compact(None, 1, 64, 0x1000, 0x1000, 0x1000, None, 0, None) == INVALID
     assert L.svdp_compact(0x1000, 1, 100, 0x1000, 0x1000, 0x1000, None, 0, None) == UNSUPPORTED
     assert L.svdp_stack_glue(None, 0x1000, 0x1000, 64, 0, 1e-6, 0x1000, None) == INVALID
-    assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, None, 0x1000, ws, None) == INVALID
-    assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, 0x1000, 0x1000, 64, None) == WORKSPACE
+    assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, None, None, 0x1000, ws, None) == INVALID
+    assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, 0x1000, 0x1004, 0x1000, ws, None) == INVALID
+    assert L.svdp_active_rows(ctypes.byref(l), 0x1000, 1, 0x1000, None, 0x1000, 64, None) == WORKSPACE
 
 
 def test_library_has_no_process_wide_switches(svdp):

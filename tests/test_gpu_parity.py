@@ -246,26 +246,30 @@ def test_step_equals_separate_calls(env):
         assert torch.equal(y, y_sep)
 
 
-def test_active_rows_stage_alone(env):
-    """svdp_active_rows (stage 3 alone, used to time the dominant kernel): the partial y's it
-    leaves in the workspace add up to the step's y."""
+def test_active_rows_from_mask_words(env):
+    """svdp_active_rows: the sparse FFN from the step's own mask words gives the step's y bit for bit, for every
+    row-kernel family (two-launch vector path, sequential pipeline, matrix cores); the form that enqueues only
+    the dominant kernel (used to time it by itself) leaves y alone and does not disturb the next full call."""
     binding, torch, oracle = env
     c = get_case(env, "tiny", d=1024, D=2560, r=72, dtype="bf16", seed=7, k_dom=32)
-    for B in (1, 4):
-        x = c.Xd[2:2 + B]
-        D, d = c.spec.D, c.spec.d
-        mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
-        nnz = torch.zeros(1, dtype=torch.int32, device="cuda")
-        ws = torch.zeros(binding.workspace_bytes(c.dev, B), dtype=torch.uint8, device="cuda")
-        y = binding.ffn_step(c.dev, x, ws=ws, mask=mask, nnz=nnz).clone()
-        ws.zero_()
-        binding.active_rows(c.dev, x, mask, ws=ws)
-        torch.cuda.synchronize()
-        # the partial y's are the last region of the workspace: [256 blocks][NB][d] fp32, unused ones zero here
-        NB = 1 if B == 1 else 4
-        part = ws[-256 * NB * d * 4:].view(torch.float32).view(256, NB, d)[:, :B].double().sum(dim=0)
-        assert torch.allclose(part.float(), y, rtol=1e-4, atol=1e-5 * float(y.abs().max()))
-        assert torch.equal(binding.ffn_step(c.dev, x, ws=ws), y)
+    for flags in (0, binding.FLAG_REVALIDATE, binding.FLAG_ENGINE_MATRIX):
+        dev = c.dev.with_flags(flags)
+        for B in (1, 4, 8):
+            x = c.Xd[2:2 + B]
+            D = c.spec.D
+            mask = torch.zeros(D // 64, dtype=torch.int64, device="cuda")
+            ws = torch.zeros(binding.workspace_bytes(dev, B), dtype=torch.uint8, device="cuda")
+            y = binding.ffn_step(dev, x, ws=ws, mask=mask).clone()
+            ws.zero_()
+            y2 = torch.full_like(y, 7.0)
+            binding.active_rows(dev, x, mask, ws=ws, out=y2)
+            assert torch.equal(y2, y)
+            y3 = torch.full_like(y, 7.0)
+            assert binding.active_rows(dev, x, mask, ws=ws, first_kernel_only=True) is None
+            torch.cuda.synchronize()
+            assert bool((y3 == 7.0).all())
+            binding.active_rows(dev, x, mask, ws=ws, out=y3)
+            assert torch.equal(y3, y)
 
 
 def test_flags_drelu_and_revalidate(env):
