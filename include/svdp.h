@@ -11,7 +11,8 @@
  *
  * Common rules for every call that takes a stream:
  *  - asynchronous on `stream` (a hipStream_t passed as void*, NULL = default
- *    stream); the call never synchronises, never allocates device memory and
+ *    stream); the call never synchronises (svdp_whiten_factors, an offline step,
+ *    is the one exception and says so), never allocates device memory and
  *    never copies device data to the host, so it can be captured in a HIP graph;
  *  - arguments are validated on the host first; on any error nothing is
  *    enqueued and a status other than SVDP_OK is returned;
@@ -228,6 +229,30 @@ svdp_status svdp_calib_stats(const svdp_layer *layer, const void *X, int32_t T, 
 svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T, int32_t eta, int64_t need,
                             float *b, int32_t *k, int32_t *steps, float *kendall,
                             void *ws, size_t ws_bytes, void *stream);
+
+/* ---- offline build: predictor factors with data whitening (Sec. 4.1, Alg. 1) ----
+ *
+ * From the gate matrix W_gate [D][d] and T calibration tokens X [T][d] (both device, in `wdtype`):
+ * with S any factor of the tokens' second moments, S S^T = X^T X, and U Sigma V^T the SVD of W_gate S,
+ * the rank-r pair A = U_r Sigma_r, B = V_r^T S^-1 minimises ||(W_gate - A B) X^T||_F over rank-r products.
+ * Outputs in the library's letters, fp32, device: Q = A [D][r], P = B^T [d][r], so that the predictor's
+ * scores are (x P) Q^T; the caller rounds them to the layer's storage type.  sigma [r] (host, nullable):
+ * the r leading singular values of W_gate S, descending.  sweeps [2] (host, nullable): Jacobi sweeps the
+ * two eigen-decompositions took.
+ * The product A B does not depend on which factor S is taken (Alg. 1 prints the Cholesky factor); here
+ * S = E Lambda^1/2 from the symmetric eigen-decomposition X^T X = E Lambda E^T, so that one eigen-solver
+ * serves both factorisations and S^-1 = Lambda^-1/2 E^T needs no triangular solve.  All arithmetic is
+ * fp64: contractions on the matrix cores, the two d x d eigen-decompositions by cyclic Jacobi sweeps.
+ * Needs d a multiple of 64, T >= d and X^T X positive definite (smallest eigenvalue > 1e-12 of the
+ * largest), r <= d; otherwise SVDP_ERR_UNSUPPORTED.
+ * Unlike the decode calls this one is an offline step: it SYNCHRONISES `stream` several times (it reads
+ * convergence figures and eigenvalues on the host) and cannot be captured in a graph.  It allocates
+ * nothing on the device.  ws: device, 256-byte aligned, >= svdp_whiten_workspace_bytes(d, D, T, r)
+ * (0 for sizes it does not take).                                                                      */
+size_t svdp_whiten_workspace_bytes(int32_t d, int32_t D, int32_t T, int32_t r);
+svdp_status svdp_whiten_factors(const void *W_gate, const void *X, int32_t d, int32_t D, int32_t T, int32_t r,
+                                int32_t wdtype, float *P, float *Q, float *sigma, int32_t *sweeps,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /* svdp_ffn_step with svdp_stack_glue in front of it, in the same launches: the step's token is
  * x = RMSNorm(x_prev + y_prev) + shift rounded to `wdtype` (bit for bit what svdp_stack_glue writes),

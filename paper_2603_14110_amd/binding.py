@@ -26,6 +26,7 @@ EXPORTS = [
     "svdp_ffn_step", "svdp_ffn_step_static", "svdp_stack_glue", "svdp_status_string", "svdp_version",
     "svdp_active_rows", "svdp_calib_workspace_bytes", "svdp_calib_need", "svdp_calib_bias",
     "svdp_calib_stats_workspace_bytes", "svdp_calib_stats", "svdp_ffn_step_glued",
+    "svdp_whiten_workspace_bytes", "svdp_whiten_factors",
 ]
 
 
@@ -84,6 +85,11 @@ def lib() -> ctypes.CDLL:
     L.svdp_calib_stats_workspace_bytes.restype = ctypes.c_size_t
     L.svdp_calib_stats.argtypes = [lp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
     L.svdp_calib_stats.restype = ctypes.c_int
+    L.svdp_whiten_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    L.svdp_whiten_workspace_bytes.restype = ctypes.c_size_t
+    L.svdp_whiten_factors.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_float),
+                                      ctypes.POINTER(ctypes.c_int32), vp, ctypes.c_size_t, vp]
+    L.svdp_whiten_factors.restype = ctypes.c_int
     L.svdp_ffn_step_glued.argtypes = [lp, vp, vp, vp, ctypes.c_float, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     L.svdp_ffn_step_glued.restype = ctypes.c_int
     _lib = L
@@ -321,6 +327,27 @@ def calib_bias(w: torch.Tensor, s: torch.Tensor, eta: int, need: int, want_kenda
     _check(lib().svdp_calib_bias(_ptr(w), _ptr(s), D, T, int(eta), int(need), _ptr(b), _ptr(k), _ptr(steps),
                                  _ptr(kend), _ptr(ws), ws.numel(), _stream()), "svdp_calib_bias")
     return b, k, steps, kend
+
+
+def whiten_factors(W_gate: torch.Tensor, X: torch.Tensor, r: int):
+    """Predictor factors with data whitening (Alg. 1) for W_gate [D][d] and calibration tokens X [T][d] (device,
+    both float32 or both bfloat16).  Returns (P [d][r] fp32, Q [D][r] fp32, sigma [r] numpy, sweeps (2 ints))."""
+    assert W_gate.dim() == 2 and X.dim() == 2 and W_gate.dtype == X.dtype and W_gate.shape[1] == X.shape[1]
+    assert W_gate.is_cuda and X.is_cuda and W_gate.is_contiguous() and X.is_contiguous()
+    D, d = W_gate.shape
+    T = X.shape[0]
+    dt = SVDP_BF16 if W_gate.dtype == torch.bfloat16 else SVDP_F32
+    nbytes = lib().svdp_whiten_workspace_bytes(d, D, T, int(r))
+    if nbytes == 0:
+        raise SvdpError(f"svdp_whiten_factors: unsupported sizes d={d} D={D} T={T} r={r}")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=X.device)
+    P = torch.empty((d, r), dtype=torch.float32, device=X.device)
+    Q = torch.empty((D, r), dtype=torch.float32, device=X.device)
+    sigma = (ctypes.c_float * int(r))()
+    sweeps = (ctypes.c_int32 * 2)()
+    _check(lib().svdp_whiten_factors(_ptr(W_gate), _ptr(X), d, D, T, int(r), dt, _ptr(P), _ptr(Q), sigma, sweeps,
+                                     _ptr(ws), ws.numel(), _stream()), "svdp_whiten_factors")
+    return P, Q, np.array(sigma[:], dtype=np.float32), (int(sweeps[0]), int(sweeps[1]))
 
 
 def version() -> str:

@@ -10,11 +10,15 @@
 #include "svdp_rows_seq.h"
 #include "svdp_calib.h"
 #include "svdp_calib_stats.h"
+#include "svdp_whiten.h"
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
+#include <numeric>
 #include <mutex>
 #include <type_traits>
+#include <vector>
 
 namespace {
 
@@ -459,6 +463,164 @@ void *static_scratch()
     return p;
 }
 
+// ---- offline build with whitening (Alg. 1): fp64 work buffers and the Jacobi driver ----
+struct WhitenWs {
+    double *W64, *M, *Mt;       // [D][d], [D][d], [d][D]
+    double *Xt;                 // [d][T]
+    double *A0, *A1;            // [d][d] symmetric matrix, ping-pong
+    double *V0, *V1;            // [d][d] eigenvectors as rows, ping-pong
+    double *St;                 // [d][d]  S^T = sqrt(lambda) * E^T
+    double *E;                  // [d][d]  E (eigenvectors of X^T X as columns)
+    double *lamC, *lamG;        // [d] eigenvalues by place
+    double *Vr;                 // [r][d]
+    double *out64;              // [max(D, d)][r]
+    double *cs, *rowsums, *sums;
+    int32_t *sel;               // [r]
+    size_t bytes;
+};
+
+WhitenWs carve_whiten(void *base, int d, int D, int T, int r)
+{
+    WhitenWs w;
+    char *p = static_cast<char *>(base);
+    size_t off = 0;
+    auto take = [&](size_t n_doubles) {
+        double *q = reinterpret_cast<double *>(p + off);
+        off += align_up(n_doubles * 8);
+        return q;
+    };
+    const size_t dd = (size_t)d * d, Dd = (size_t)D * d;
+    w.W64 = take(Dd);
+    w.M = take(Dd);
+    w.Mt = take(Dd);
+    w.Xt = take((size_t)d * T);
+    w.A0 = take(dd);
+    w.A1 = take(dd);
+    w.V0 = take(dd);
+    w.V1 = take(dd);
+    w.St = take(dd);
+    w.E = take(dd);
+    w.lamC = take(d);
+    w.lamG = take(d);
+    w.Vr = take((size_t)r * d);
+    w.out64 = take((size_t)(D > d ? D : d) * r);
+    w.cs = take(d);
+    w.rowsums = take((size_t)2 * d);
+    w.sums = take(2);
+    w.sel = reinterpret_cast<int32_t *>(p + off);
+    off += align_up((size_t)r * 4);
+    w.bytes = off;
+    return w;
+}
+
+inline dim3 grid1(size_t n) { return dim3((unsigned)((n + 255) / 256)); }
+
+void dgemm_nt(const double *A, int lda, const double *Bm, int ldb, double *C, int ldc, int M, int N, int K, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_dgemm_nt, dim3((N + DG_BN - 1) / DG_BN, (M + DG_BM - 1) / DG_BM), dim3(256), 0, st, A, lda, Bm, ldb,
+                       C, ldc, M, N, K);
+}
+
+// Eigen-decomposition of the symmetric matrix in *A (n x n, n % 64 == 0) by cyclic Jacobi sweeps.  On return
+// *A / *V point at the buffers holding the (numerically) diagonal matrix and the eigenvectors as rows, lam[i]
+// (device) = (*A)[i][i].  Synchronises the stream once per sweep (the convergence figure is read on the host).
+svdp_status jacobi_eigh(double **A, double **Aalt, double **V, double **Valt, int n, double *cs, double *rowsums,
+                        double *sums, double *lam, double tol, int max_sweeps, int *sweeps_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_identity, grid1((size_t)n * n), dim3(256), 0, st, *V, n);
+    int sweep = 0;
+    for (;; ++sweep) {
+        hipLaunchKernelGGL(k_jacobi_norms, dim3(n), dim3(256), 0, st, *A, n, rowsums);
+        hipLaunchKernelGGL(k_jacobi_norms_finish, dim3(1), dim3(256), 0, st, rowsums, n, *A, sums, lam);
+        double h[2] = {0.0, 0.0};
+        if (hipMemcpyAsync(h, sums, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess) {
+            (void)hipGetLastError();
+            return SVDP_ERR_HIP;
+        }
+        if (!(h[1] == h[1]) || h[0] <= tol * tol * h[1] || sweep >= max_sweeps) break;
+        for (int step = 0; step < n - 1; ++step) {
+            hipLaunchKernelGGL(k_jacobi_angles, grid1((size_t)n / 2), dim3(256), 0, st, *A, n, cs);
+            hipLaunchKernelGGL(k_jacobi_rotate, dim3(n / 64, n / 64), dim3(256), 0, st, *A, cs, n, *Aalt);
+            hipLaunchKernelGGL(k_jacobi_rows, dim3(n / 2), dim3(256), 0, st, *V, cs, n, *Valt);
+            std::swap(*A, *Aalt);
+            std::swap(*V, *Valt);
+        }
+    }
+    if (sweeps_out != nullptr) *sweeps_out = sweep;
+    return hip_status(hipSuccess);
+}
+
+template <typename W>
+svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, int r, float *P, float *Q, float *sigma,
+                        int32_t *sweeps, const WhitenWs &w, hipStream_t st)
+{
+    const W *Wg = static_cast<const W *>(W_gate), *Xs = static_cast<const W *>(X);
+    const double tol = 1e-11;          // off-diagonal Frobenius norm relative to the matrix's
+    const int max_sweeps = 24;
+    std::vector<double> lam(d);
+    std::vector<int32_t> order(d);
+
+    // second moments C = X^T X  (d x d)
+    hipLaunchKernelGGL((k_transpose_to_f64<W>), dim3((d + 31) / 32, (T + 31) / 32), dim3(256), 0, st, Xs, T, d, w.Xt);
+    double *A = w.A0, *Aalt = w.A1, *V = w.V0, *Valt = w.V1;
+    dgemm_nt(w.Xt, T, w.Xt, T, A, d, d, d, T, st);
+    int sw1 = 0, sw2 = 0;
+    svdp_status e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.cs, w.rowsums, w.sums, w.lamC, tol, max_sweeps, &sw1, st);
+    if (e != SVDP_OK) return e;
+    if (hipMemcpyAsync(lam.data(), w.lamC, (size_t)d * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        (void)hipGetLastError();
+        return SVDP_ERR_HIP;
+    }
+    // S S^T = C needs C positive definite (more independent tokens than dimensions)
+    const double lmax = *std::max_element(lam.begin(), lam.end()), lmin = *std::min_element(lam.begin(), lam.end());
+    if (!(lmax > 0.0) || !(lmin > 1e-12 * lmax)) return SVDP_ERR_UNSUPPORTED;
+    // S = E sqrt(Lambda): S^T = rows of E^T scaled; E itself for P at the end
+    hipLaunchKernelGGL(k_scale_rows<1>, grid1((size_t)d * d), dim3(256), 0, st, V, w.lamC, d, d, w.St);
+    hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (d + 31) / 32), dim3(256), 0, st, V, d, d, w.E);
+
+    // M = W_gate S, G = M^T M
+    hipLaunchKernelGGL((k_to_f64<W>), grid1((size_t)D * d), dim3(256), 0, st, Wg, (size_t)D * d, w.W64);
+    dgemm_nt(w.W64, d, w.St, d, w.M, d, D, d, d, st);
+    hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (D + 31) / 32), dim3(256), 0, st, w.M, D, d, w.Mt);
+    A = w.A0; Aalt = w.A1; V = w.V0; Valt = w.V1;
+    dgemm_nt(w.Mt, D, w.Mt, D, A, d, d, d, D, st);
+    e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.cs, w.rowsums, w.sums, w.lamG, tol, max_sweeps, &sw2, st);
+    if (e != SVDP_OK) return e;
+    if (hipMemcpyAsync(lam.data(), w.lamG, (size_t)d * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        (void)hipGetLastError();
+        return SVDP_ERR_HIP;
+    }
+    // the r largest eigenvalues (= squared singular values of W S), largest first; ties by place
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return lam[a] > lam[b]; });
+    if (hipMemcpyAsync(w.sel, order.data(), (size_t)r * 4, hipMemcpyHostToDevice, st) != hipSuccess) {
+        (void)hipGetLastError();
+        return SVDP_ERR_HIP;
+    }
+    // Q = A = M V_r
+    hipLaunchKernelGGL(k_gather_rows, grid1((size_t)r * d), dim3(256), 0, st, V, w.sel, r, d, nullptr, w.Vr);
+    dgemm_nt(w.M, d, w.Vr, d, w.out64, r, D, r, d, st);
+    hipLaunchKernelGGL(k_f64_to_f32, grid1((size_t)D * r), dim3(256), 0, st, w.out64, (size_t)D * r, Q);
+    // P = B^T = S^-T V_r = E Lambda^-1/2 V_r
+    hipLaunchKernelGGL(k_gather_rows, grid1((size_t)r * d), dim3(256), 0, st, V, w.sel, r, d, w.lamC, w.Vr);
+    dgemm_nt(w.E, d, w.Vr, d, w.out64, r, d, r, d, st);
+    hipLaunchKernelGGL(k_f64_to_f32, grid1((size_t)d * r), dim3(256), 0, st, w.out64, (size_t)d * r, P);
+    if (hipStreamSynchronize(st) != hipSuccess) {                 // order[] leaves scope: the copy above must be done
+        (void)hipGetLastError();
+        return SVDP_ERR_HIP;
+    }
+    if (sigma != nullptr)
+        for (int k = 0; k < r; ++k) sigma[k] = (float)std::sqrt(std::max(lam[order[k]], 0.0));
+    if (sweeps != nullptr) {
+        sweeps[0] = sw1;
+        sweeps[1] = sw2;
+    }
+    return hip_status(hipSuccess);
+}
+
 }  // namespace
 
 extern "C" {
@@ -758,6 +920,28 @@ svdp_status svdp_calib_stats(const svdp_layer *layer, const void *X, int32_t T, 
     return hip_status(hipSuccess);
 }
 
-const char *svdp_version(void) { return "0.4"; }
+size_t svdp_whiten_workspace_bytes(int32_t d, int32_t D, int32_t T, int32_t r)
+{
+    if (d < 64 || d % 64 != 0 || D < 1 || T < d || r < 1 || r > d) return 0;
+    return carve_whiten(nullptr, d, D, T, r).bytes;
+}
+
+svdp_status svdp_whiten_factors(const void *W_gate, const void *X, int32_t d, int32_t D, int32_t T, int32_t r,
+                                int32_t wdtype, float *P, float *Q, float *sigma, int32_t *sweeps, void *ws,
+                                size_t ws_bytes, void *stream)
+{
+    if (W_gate == nullptr || X == nullptr || P == nullptr || Q == nullptr || d < 1 || D < 1 || T < 1 || r < 1)
+        return SVDP_ERR_INVALID_ARG;
+    if (wdtype != SVDP_F32 && wdtype != SVDP_BF16) return SVDP_ERR_UNSUPPORTED;
+    if (d < 64 || d % 64 != 0 || T < d || r > d) return SVDP_ERR_UNSUPPORTED;
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & (ALIGN - 1))) return SVDP_ERR_WORKSPACE;
+    const WhitenWs w = carve_whiten(ws, d, D, T, r);
+    if (ws_bytes < w.bytes) return SVDP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (wdtype == SVDP_F32) return whiten_impl<float>(W_gate, X, d, D, T, r, P, Q, sigma, sweeps, w, st);
+    return whiten_impl<bf16>(W_gate, X, d, D, T, r, P, Q, sigma, sweeps, w, st);
+}
+
+const char *svdp_version(void) { return "0.5"; }
 
 }  // extern "C"

@@ -185,6 +185,28 @@ def test_calib_need_is_the_oracles_rule(svdp):
     assert L.svdp_calib_need(0.5, 0, 4) == -1 and L.svdp_calib_need(float("nan"), 4, 4) == -1
 
 
+def test_whitening_entry_points_validate_on_the_host(svdp):
+    L = svdp.lib()
+    a = 0x1000
+    INVALID, UNSUPPORTED, WORKSPACE = 1, 2, 3
+    n = L.svdp_whiten_workspace_bytes(4096, 11008, 8192, 256)
+    # fp64 copies of W, W S and its transpose, the tokens, two ping-pong pairs of d x d matrices, S^T and E
+    assert n % 256 == 0 and n >= 8 * (3 * 11008 * 4096 + 4096 * 8192 + 6 * 4096 * 4096)
+    for bad in ((4000, 11008, 8192, 256), (4096, 0, 8192, 256), (4096, 11008, 4095, 256), (4096, 11008, 8192, 0),
+                (4096, 11008, 8192, 5000), (32, 64, 64, 8)):
+        assert L.svdp_whiten_workspace_bytes(*bad) == 0, bad
+    args = lambda **o: [o.get("W", a), o.get("X", a), o.get("d", 128), 256, o.get("T", 512), o.get("r", 8), o.get("dt", 1),
+                        o.get("P", a), a, None, None, o.get("ws", a), o.get("n", 1 << 30), None]
+    assert L.svdp_whiten_factors(*args(W=None)) == INVALID
+    assert L.svdp_whiten_factors(*args(P=None)) == INVALID
+    assert L.svdp_whiten_factors(*args(dt=5)) == UNSUPPORTED
+    assert L.svdp_whiten_factors(*args(d=96)) == UNSUPPORTED
+    assert L.svdp_whiten_factors(*args(T=100)) == UNSUPPORTED
+    assert L.svdp_whiten_factors(*args(ws=None)) == WORKSPACE
+    assert L.svdp_whiten_factors(*args(ws=0x1010)) == WORKSPACE
+    assert L.svdp_whiten_factors(*args(n=1024)) == WORKSPACE
+
+
 def test_calibration_entry_points_validate_on_the_host(svdp):
     L = svdp.lib()
     INVALID, UNSUPPORTED, WORKSPACE = 1, 2, 3

@@ -236,9 +236,9 @@ def test_full_size_layer_as_benchmarked(env):
 
 
 def test_offline_build_then_decode(env, oracle):
-    """The method end to end on one small layer: factors from the whitened factorisation (Alg. 1, the oracle's,
-    on correlated calibration tokens), bias from the greedy calibration on the GPU (Alg. 2), then the decode
-    step on held-out tokens.  Checks what the construction promises: the calibration set is dropped at exactly
+    """The method end to end on one small layer, every stage on the GPU: factors from the whitened factorisation
+    (Alg. 1, svdp_whiten_factors, on correlated calibration tokens), bias from the greedy calibration (Alg. 2),
+    then the decode step on held-out tokens.  Checks what the construction promises: the calibration set is dropped at exactly
     the requested level, the predictor built with whitening loses less damage than the plain truncation at the
     same rank and sparsity level, and the sparse output stays close to the dense one."""
     binding, torch, calib = env
@@ -256,7 +256,8 @@ def test_offline_build_then_decode(env, oracle):
     lost, dens, outs = {}, {}, {}
     for name in ("whitened", "plain"):
         if name == "whitened":
-            A, B = calib.whitened_factors(f32(Wg), f32(Xcal), r)
+            Pw, Qw, _, _ = binding.whiten_factors(binding.to_device(Wg, "bf16"), binding.to_device(Xcal, "bf16"), r)
+            A, B = Qw.cpu().numpy().astype(np.float64), Pw.cpu().numpy().astype(np.float64).T
         else:
             U, sv, Vt = np.linalg.svd(f32(Wg).astype(np.float64), full_matrices=False)
             A, B = U[:, :r] * sv[:r], Vt[:r]
