@@ -474,7 +474,7 @@ struct WhitenWs {
     double *lamC, *lamG;        // [d] eigenvalues by place
     double *Vr;                 // [r][d]
     double *out64;              // [max(D, d)][r]
-    double *cs, *rowsums, *sums;
+    double *Uall, *rowsums, *sums;     // [d/64][64][64] strip transforms; norms
     int32_t *sel;               // [r]
     size_t bytes;
 };
@@ -504,7 +504,7 @@ WhitenWs carve_whiten(void *base, int d, int D, int T, int r)
     w.lamG = take(d);
     w.Vr = take((size_t)r * d);
     w.out64 = take((size_t)(D > d ? D : d) * r);
-    w.cs = take(d);
+    w.Uall = take((size_t)d * 64);
     w.rowsums = take((size_t)2 * d);
     w.sums = take(2);
     w.sel = reinterpret_cast<int32_t *>(p + off);
@@ -521,13 +521,21 @@ void dgemm_nt(const double *A, int lda, const double *Bm, int ldb, double *C, in
                        C, ldc, M, N, K);
 }
 
-// Eigen-decomposition of the symmetric matrix in *A (n x n, n % 64 == 0) by cyclic Jacobi sweeps.  On return
+// Eigen-decomposition of the symmetric matrix in *A (n x n, n % 64 == 0) by block Jacobi sweeps.  On return
 // *A / *V point at the buffers holding the (numerically) diagonal matrix and the eigenvectors as rows, lam[i]
-// (device) = (*A)[i][i].  Synchronises the stream once per sweep (the convergence figure is read on the host).
-svdp_status jacobi_eigh(double **A, double **Aalt, double **V, double **Valt, int n, double *cs, double *rowsums,
+// (device) = (*A)[i][i].  Uall: n/64 matrices of 64 x 64.  Synchronises the stream once per sweep (the
+// convergence figure is read on the host).
+svdp_status jacobi_eigh(double **A, double **Aalt, double **V, double **Valt, int n, double *Uall, double *rowsums,
                         double *sums, double *lam, double tol, int max_sweeps, int *sweeps_out, hipStream_t st)
 {
+    const size_t lds_solve = (size_t)2 * BJ_S * BJ_LD * 8, lds_two = (size_t)2 * BJ_S * BJ_LD * 8,
+                 lds_one = lds_two;
+    if (!grant_lds<k_bjacobi_solve>(lds_solve) || !grant_lds<k_bjacobi_apply<true>>(lds_two) ||
+        !grant_lds<k_bjacobi_apply<false>>(lds_one))
+        return SVDP_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(k_identity, grid1((size_t)n * n), dim3(256), 0, st, *V, n);
+    const int strips = n / BJ_S, rounds = n / BJ_B > 2 ? n / BJ_B - 1 : 1;
+    const int ct = strips >= 32 ? 4 : 1, cgrid = (strips + ct - 1) / ct;      // column tiles per block
     int sweep = 0;
     for (;; ++sweep) {
         hipLaunchKernelGGL(k_jacobi_norms, dim3(n), dim3(256), 0, st, *A, n, rowsums);
@@ -539,10 +547,10 @@ svdp_status jacobi_eigh(double **A, double **Aalt, double **V, double **Valt, in
             return SVDP_ERR_HIP;
         }
         if (!(h[1] == h[1]) || h[0] <= tol * tol * h[1] || sweep >= max_sweeps) break;
-        for (int step = 0; step < n - 1; ++step) {
-            hipLaunchKernelGGL(k_jacobi_angles, grid1((size_t)n / 2), dim3(256), 0, st, *A, n, cs);
-            hipLaunchKernelGGL(k_jacobi_rotate, dim3(n / 64, n / 64), dim3(256), 0, st, *A, cs, n, *Aalt);
-            hipLaunchKernelGGL(k_jacobi_rows, dim3(n / 2), dim3(256), 0, st, *V, cs, n, *Valt);
+        for (int round = 0; round < rounds; ++round) {
+            hipLaunchKernelGGL(k_bjacobi_solve, dim3(strips), dim3(BJ_SOLVE_THREADS), lds_solve, st, *A, n, Uall);
+            hipLaunchKernelGGL(k_bjacobi_apply<true>, dim3(cgrid, strips), dim3(256), lds_two, st, *A, Uall, n, ct, *Aalt);
+            hipLaunchKernelGGL(k_bjacobi_apply<false>, dim3(cgrid, strips), dim3(256), lds_one, st, *V, Uall, n, ct, *Valt);
             std::swap(*A, *Aalt);
             std::swap(*V, *Valt);
         }
@@ -566,7 +574,7 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
     double *A = w.A0, *Aalt = w.A1, *V = w.V0, *Valt = w.V1;
     dgemm_nt(w.Xt, T, w.Xt, T, A, d, d, d, T, st);
     int sw1 = 0, sw2 = 0;
-    svdp_status e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.cs, w.rowsums, w.sums, w.lamC, tol, max_sweeps, &sw1, st);
+    svdp_status e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.Uall, w.rowsums, w.sums, w.lamC, tol, max_sweeps, &sw1, st);
     if (e != SVDP_OK) return e;
     if (hipMemcpyAsync(lam.data(), w.lamC, (size_t)d * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) {
@@ -586,7 +594,7 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
     hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (D + 31) / 32), dim3(256), 0, st, w.M, D, d, w.Mt);
     A = w.A0; Aalt = w.A1; V = w.V0; Valt = w.V1;
     dgemm_nt(w.Mt, D, w.Mt, D, A, d, d, d, D, st);
-    e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.cs, w.rowsums, w.sums, w.lamG, tol, max_sweeps, &sw2, st);
+    e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.Uall, w.rowsums, w.sums, w.lamG, tol, max_sweeps, &sw2, st);
     if (e != SVDP_OK) return e;
     if (hipMemcpyAsync(lam.data(), w.lamG, (size_t)d * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) {

@@ -7,11 +7,11 @@
 //
 // Everything that is a dense contraction runs on the matrix cores (k_dgemm_nt, fp64 MFMA);
 // the two symmetric d x d eigen-decompositions (of X^T X, and of (W S)^T (W S), whose
-// eigenvectors are V and eigenvalues Sigma^2) are a cyclic two-sided Jacobi method in which a
-// rotation step is ONE pass over the matrix: rows and columns that are rotated together are
-// neighbours in memory, so a 64 x 64 tile needs only its own elements and the angles of its 32
-// row pairs and 32 column pairs, and the tile is written to the places the round-robin pairing
-// wants its rows and columns in for the next step.
+// eigenvectors are V and eigenvalues Sigma^2) are a two-sided BLOCK Jacobi method in which a round
+// is ONE pass over the matrix: the blocks of rows and columns that are transformed together are
+// neighbours in memory, so a 64 x 64 tile needs only its own elements and the two small orthogonal
+// matrices of its row strip and column strip (products on the matrix cores), and the tile is
+// written to the places the round-robin pairing wants its blocks in for the next round.
 #pragma once
 
 #include "svdp_device.h"
@@ -153,100 +153,322 @@ __global__ __launch_bounds__(256) void k_dgemm_nt(const double *__restrict__ A, 
 }
 
 // ---------------------------------------------------------------------------
-// Cyclic Jacobi for a symmetric matrix A [n][n] (n a multiple of 64), eigenvectors accumulated
-// as rows of Vt (Vt starts as the identity; at the end A is diagonal up to the tolerance and row
-// i of Vt is the eigenvector of A[i][i]).
+// Block Jacobi for a symmetric matrix A [n][n] (n a multiple of 64), eigenvectors accumulated as
+// rows of Vt (Vt starts as the identity; at the end A is diagonal up to the tolerance and row i of
+// Vt is the eigenvector of A[i][i]).
 //
-// One step rotates the n/2 disjoint pairs (2k, 2k+1): A <- J^T A J, Vt <- J^T Vt with
-// J = diag of [[c, s], [-s, c]] blocks, the angle of a pair chosen to annihilate A[2k][2k+1].
-// The round-robin tournament then needs new neighbours: index 0 stays, an odd index 2k+1 moves to
-// 2k-1 (index 1 to 2), an even index 2k to 2k+2 (the last even one to n-1).  The kernels write
-// their results straight to those places, so that after n-1 steps every pair has met once (one
-// sweep) and no separate permutation pass exists.
+// The matrix is cut into blocks of 32 rows / columns.  One round pairs the blocks (2k, 2k+1) -
+// always neighbours, so a pair is the contiguous strip of rows 64k .. 64k+63 - and
+//   k_bjacobi_solve  runs a cyclic Jacobi sweep (all 2016 pairs of its 64 indices) over every strip's own
+//                    64 x 64 diagonal tile in LDS and stores the accumulated orthogonal U_k;
+//   k_bjacobi_apply  forms A <- U^T A U tile by tile (the tile of strip a and strip c needs only
+//                    itself, U_a and U_c: two 64 x 64 x 64 products on the fp64 matrix cores) and
+//                    Vt <- U^T Vt (one product), and writes every tile straight to the place the
+//                    round-robin tournament wants its blocks in for the next round: block 0 stays,
+//                    an odd block 2k+1 moves to 2k-1 (block 1 to 2), an even block 2k to 2k+2 (the
+//                    last even one to the last place).  After nblocks-1 rounds every pair of blocks
+//                    has met once (one sweep); no separate permutation pass exists.
+// Against rotating single rows and columns this moves the matrix once per 32 of them.
 // ---------------------------------------------------------------------------
+constexpr int BJ_B = 32;                 // block size
+constexpr int BJ_S = 2 * BJ_B;           // strip / tile size
+constexpr int BJ_LD = BJ_S + 1;          // LDS row stride in doubles
+// Sweeps over a diagonal tile per round.  More of them bring the tile closer to diagonal but not the matrix:
+// on the 4096 x 4096 matrices of the 7B layer the number of outer sweeps stayed 12 to 13 for 1, 2, 4 and 12
+// (to convergence) inner sweeps, while the whole factorisation took 0.94, 1.16, 1.46 and 2.29 s.
+constexpr int BJ_INNER_SWEEPS = 1;
+
 __device__ __forceinline__ int jacobi_next_place(int i, int n)
 {
-    if (i == 0) return 0;
+    if (n <= 2 || i == 0) return i;
     if (i & 1) return i == 1 ? 2 : i - 2;
     return i == n - 2 ? n - 1 : i + 2;
 }
-
-// (c, s) of every pair from the 2 x 2 diagonal blocks (the symmetric Schur decomposition)
-__global__ __launch_bounds__(256) void k_jacobi_angles(const double *__restrict__ A, int n, double *__restrict__ cs)
+// row or column index -> its place after this round (blocks move, offsets inside a block stay)
+__device__ __forceinline__ int bjacobi_next_index(int i, int n)
 {
-    const int k = blockIdx.x * 256 + threadIdx.x;
-    if (k >= n / 2) return;
-    const int p = 2 * k, q = p + 1;
-    const double app = A[(size_t)p * n + p], aqq = A[(size_t)q * n + q], apq = A[(size_t)p * n + q];
-    double c = 1.0, s = 0.0;
-    if (apq != 0.0) {
-        const double tau = (aqq - app) / (2.0 * apq);
-        const double t = tau >= 0.0 ? 1.0 / (tau + sqrt(1.0 + tau * tau)) : -1.0 / (-tau + sqrt(1.0 + tau * tau));
-        c = 1.0 / sqrt(1.0 + t * t);
-        s = t * c;
-    }
-    cs[2 * k] = c;
-    cs[2 * k + 1] = s;
+    return jacobi_next_place(i / BJ_B, n / BJ_B) * BJ_B + i % BJ_B;
 }
 
-// out[place(i)][place(j)] = (J^T A J)[i][j] for one 64 x 64 tile
-__global__ __launch_bounds__(256) void k_jacobi_rotate(const double *__restrict__ A, const double *__restrict__ cs, int n,
-                                                       double *__restrict__ out)
+// Round-robin tournament over 64 indices: seat 0 holds index 0, seat i >= 1 holds 1 + (i - 1 + step) mod 63, and
+// the pairs of a step are the seats (m, 63 - m), m = 0 .. 31.  bj_seat gives a seat's index in step 0, bj_advance
+// the index the same seat holds one step later.
+__device__ __forceinline__ int bj_seat(int seat) { return seat; }
+__device__ __forceinline__ int bj_advance(int idx) { return idx == 0 ? 0 : (idx == BJ_S - 1 ? 1 : idx + 1); }
+
+// (c, s) of the rotation J = [c s; -s c] that (nearly) zeroes the off-diagonal element of [app apq; apq aqq] in
+// J^T . J.  The tangent is worked out in single precision with the hardware's reciprocal and square root - its
+// error only leaves a residue of about 1e-7 of the element, which the next sweep removes - and (c, s) from it in
+// double precision (reciprocal square root refined by two Newton steps), so that c^2 + s^2 = 1 to rounding and
+// the accumulated transform stays orthogonal.  This sits on the critical path of every step: it is a few dozen
+// instructions, not the several hundred of IEEE double divisions and square roots.
+__device__ __forceinline__ void bj_angle(double app, double aqq, double apq, double &c, double &s)
 {
-    __shared__ double tile[64][65];
-    __shared__ double rc[32], rs[32], cc[32], csn[32];
-    const int tid = threadIdx.x;
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-    if (tid < 32) {
-        rc[tid] = cs[r0 + 2 * tid];
-        rs[tid] = cs[r0 + 2 * tid + 1];
-    } else if (tid < 64) {
-        cc[tid - 32] = cs[c0 + 2 * (tid - 32)];
-        csn[tid - 32] = cs[c0 + 2 * (tid - 32) + 1];
+    const float num = (float)(aqq - app), den = 2.0f * (float)apq;
+    const float tau = num * __builtin_amdgcn_rcpf(den);                      // den == 0: +-inf or NaN
+    const float root = __builtin_amdgcn_sqrtf(__builtin_fmaf(tau, tau, 1.0f));
+    float t = __builtin_copysignf(__builtin_amdgcn_rcpf(__builtin_fabsf(tau) + root), tau);   // |tau| = inf: 0
+    if (!(t == t) || den == 0.0f) t = 0.0f;
+    const double td = (double)t, a = __builtin_fma(td, td, 1.0);            // a in [1, 2]
+    double y = __builtin_amdgcn_rsq(a);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const double e = __builtin_fma(-a * y, y, 1.0);                     // 1 - a y^2
+        y = __builtin_fma(0.5 * y, e, y);
     }
-    for (int e = tid; e < 64 * 64; e += 256) {
+    c = y;
+    s = td * y;
+}
+
+// the value the neighbouring lane (lane ^ 1) holds, through the data-parallel path (no LDS round trip)
+__device__ __forceinline__ double bj_neighbour(double v)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xF, 0xF, false);          // quad_perm [1, 0, 3, 2]
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// U[k] (64 x 64, row-major), the product of the rotations of BJ_INNER_SWEEPS cyclic sweeps over the k-th diagonal
+// tile S of A (the identity if S is already diagonal to rounding).  One block of 1024 threads per strip; S and U live in LDS (dynamic: 2 * 64 * 65 doubles).  A step applies its 32
+// disjoint rotations J to the whole tile in ONE pass, S <- J^T S J: a lane owns one column (of the pair lane / 2,
+// the first or second index by lane % 2), a wave takes two row pairs, rotates the two rows at its column and
+// gets the neighbour column's values from the neighbouring lane for the column rotation.  Every element is read
+// and written by exactly one lane, and a wave's 64 lanes always touch 64 different columns of one row, so the
+// accesses spread over all LDS banks.  U <- U J is the same column rotation; the angles of the next step are
+// computed (32 lanes) while the other waves are in it.
+constexpr int BJ_SOLVE_THREADS = 1024;
+__global__ __launch_bounds__(BJ_SOLVE_THREADS) void k_bjacobi_solve(const double *__restrict__ A, int n,
+                                                                    double *__restrict__ Uall)
+{
+    extern __shared__ double bj_smem[];
+    double *S = bj_smem;                       // [64][65]
+    double *U = S + BJ_S * BJ_LD;              // [64][65]
+    __shared__ double csv[2][BJ_B][2];
+    __shared__ double red[2][BJ_SOLVE_THREADS / 64];
+    __shared__ int done;
+    constexpr int WAVES = BJ_SOLVE_THREADS / 64, PAIRS = BJ_B / WAVES, ROWS = BJ_S / WAVES;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, k = blockIdx.x;
+    const int pb = lane >> 1, second = lane & 1;
+    const size_t base = (size_t)(k * BJ_S) * n + (size_t)k * BJ_S;
+    for (int e = tid; e < BJ_S * BJ_S; e += BJ_SOLVE_THREADS) {
         const int i = e >> 6, j = e & 63;
-        tile[i][j] = A[(size_t)(r0 + i) * n + c0 + j];
+        S[i * BJ_LD + j] = A[base + (size_t)i * n + j];
+        U[i * BJ_LD + j] = i == j ? 1.0 : 0.0;
     }
     __syncthreads();
-    // rows: pair k = tid / 8, eight columns each
-    {
-        const int k = tid >> 3, j0 = (tid & 7) * 8;
-        const double c = rc[k], s = rs[k];
+    for (int sweep = 0; sweep < BJ_INNER_SWEEPS; ++sweep) {
+        // converged when the off-diagonal part is at rounding level of the tile
+        double off = 0.0, all = 0.0;
+        for (int e = tid; e < BJ_S * BJ_S; e += BJ_SOLVE_THREADS) {
+            const int i = e >> 6, j = e & 63;
+            const double v = S[i * BJ_LD + j];
+            all += v * v;
+            if (i != j) off += v * v;
+        }
+        for (int w = 32; w > 0; w >>= 1) {
+            off += __shfl_xor(off, w);
+            all += __shfl_xor(all, w);
+        }
+        if (lane == 0) {
+            red[0][wave] = off;
+            red[1][wave] = all;
+        }
+        // this lane's column, this wave's row pairs and (threads 0 .. 31) the pair whose angle the thread works
+        // out, all for step 0; advanced step by step below
+        int col = second ? bj_seat(BJ_S - 1 - pb) : bj_seat(pb);
+        int rp[PAIRS], rq[PAIRS];
 #pragma unroll
-        for (int j = j0; j < j0 + 8; ++j) {
-            const double x = tile[2 * k][j], y = tile[2 * k + 1][j];
-            tile[2 * k][j] = c * x - s * y;
-            tile[2 * k + 1][j] = s * x + c * y;
+        for (int e = 0; e < PAIRS; ++e) {
+            rp[e] = bj_seat(wave * PAIRS + e);
+            rq[e] = bj_seat(BJ_S - 1 - (wave * PAIRS + e));
+        }
+        int ap = bj_seat(tid & (BJ_B - 1)), aq = bj_seat(BJ_S - 1 - (tid & (BJ_B - 1)));
+        __syncthreads();
+        if (tid == 0) {
+            double o = 0.0, t = 0.0;
+            for (int w = 0; w < WAVES; ++w) {
+                o += red[0][w];
+                t += red[1][w];
+            }
+            done = (o <= 1e-26 * t) ? 1 : 0;
+        }
+        if (tid < BJ_B) {
+            double c, s;
+            bj_angle(S[ap * BJ_LD + ap], S[aq * BJ_LD + aq], S[ap * BJ_LD + aq], c, s);
+            csv[0][tid][0] = c;
+            csv[0][tid][1] = s;
+        }
+        __syncthreads();
+        if (done) break;
+        for (int step = 0; step < BJ_S - 1; ++step) {
+            const int cur = step & 1;
+            // column rotation of a value v at this lane's column, w the same row's value at the pair's other
+            // column:  first column  c v - s w,  second column  c v + s w
+            const double cb = csv[cur][pb][0], sb = second ? csv[cur][pb][1] : -csv[cur][pb][1];
+            double x[PAIRS], y[PAIRS];
+#pragma unroll
+            for (int e = 0; e < PAIRS; ++e) {
+                x[e] = S[rp[e] * BJ_LD + col];
+                y[e] = S[rq[e] * BJ_LD + col];
+            }
+#pragma unroll
+            for (int e = 0; e < PAIRS; ++e) {
+                const double ca = csv[cur][wave * PAIRS + e][0], sa = csv[cur][wave * PAIRS + e][1];
+                const double xr = ca * x[e] - sa * y[e], yr = sa * x[e] + ca * y[e];
+                const double xo = bj_neighbour(xr), yo = bj_neighbour(yr);
+                S[rp[e] * BJ_LD + col] = cb * xr + sb * xo;
+                S[rq[e] * BJ_LD + col] = cb * yr + sb * yo;
+            }
+            __syncthreads();
+            ap = bj_advance(ap);
+            aq = bj_advance(aq);
+            if (tid < BJ_B && step + 1 < BJ_S - 1) {
+                double c, s;
+                bj_angle(S[ap * BJ_LD + ap], S[aq * BJ_LD + aq], S[ap * BJ_LD + aq], c, s);
+                csv[cur ^ 1][tid][0] = c;
+                csv[cur ^ 1][tid][1] = s;
+            }
+            double u[ROWS];
+#pragma unroll
+            for (int e = 0; e < ROWS; ++e) u[e] = U[(wave * ROWS + e) * BJ_LD + col];
+#pragma unroll
+            for (int e = 0; e < ROWS; ++e) {
+                const double uo = bj_neighbour(u[e]);
+                U[(wave * ROWS + e) * BJ_LD + col] = cb * u[e] + sb * uo;
+            }
+            col = bj_advance(col);
+#pragma unroll
+            for (int e = 0; e < PAIRS; ++e) {
+                rp[e] = bj_advance(rp[e]);
+                rq[e] = bj_advance(rq[e]);
+            }
+            __syncthreads();
         }
     }
-    __syncthreads();
-    // columns: row i = tid / 4, eight column pairs each; straight to the next step's places
-    {
-        const int i = tid >> 2, k0 = (tid & 3) * 8;
-        const size_t orow = (size_t)jacobi_next_place(r0 + i, n) * n;
-#pragma unroll
-        for (int k = k0; k < k0 + 8; ++k) {
-            const double c = cc[k], s = csn[k];
-            const double x = tile[i][2 * k], y = tile[i][2 * k + 1];
-            out[orow + jacobi_next_place(c0 + 2 * k, n)] = c * x - s * y;
-            out[orow + jacobi_next_place(c0 + 2 * k + 1, n)] = s * x + c * y;
-        }
+    for (int e = tid; e < BJ_S * BJ_S; e += BJ_SOLVE_THREADS) {
+        const int i = e >> 6, j = e & 63;
+        Uall[(size_t)k * BJ_S * BJ_S + e] = U[i * BJ_LD + j];
     }
 }
 
-// out[place(i)][:] = (J^T Vt)[i][:]: one block per row pair
-__global__ __launch_bounds__(256) void k_jacobi_rows(const double *__restrict__ Vt, const double *__restrict__ cs, int n,
-                                                     double *__restrict__ out)
+// 64 x 64 x 64 product on the matrix cores, operands in LDS:  C[i][j] = sum_k L(k, i) * R[k][j]  with
+// L(k, i) = Lm[k][i] (LT: the left factor is used transposed, U^T T) or Lm[i][k] (X U).  Wave (wm, wn) owns the
+// 32 x 32 quadrant; the result register v of a lane is C[16 ti + 4 v + lq][16 tj + lm] of its tile (ti, tj).
+template <bool LT>
+__device__ __forceinline__ void bj_mma64(const double *Lm, const double *Rm, int wm, int wn, int lm, int lq,
+                                         f64x4_t (&acc)[2][2])
 {
-    const int k = blockIdx.x;
-    const double c = cs[2 * k], s = cs[2 * k + 1];
-    const double *x = Vt + (size_t)(2 * k) * n, *y = x + n;
-    double *ox = out + (size_t)jacobi_next_place(2 * k, n) * n, *oy = out + (size_t)jacobi_next_place(2 * k + 1, n) * n;
-    for (int j = threadIdx.x; j < n; j += 256) {
-        const double a = x[j], b = y[j];
-        ox[j] = c * a - s * b;
-        oy[j] = s * a + c * b;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll 4
+    for (int kk = 0; kk < BJ_S; kk += 4) {
+        double fa[2], fb[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = wm * 32 + i * 16 + lm;
+            fa[i] = LT ? Lm[(kk + lq) * BJ_LD + row] : Lm[row * BJ_LD + kk + lq];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fb[j] = Rm[(kk + lq) * BJ_LD + wn * 32 + j * 16 + lm];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+}
+
+// TWO_SIDED: out[next(i)][next(j)] = (U_a^T T U_c)[i][j] for the tile T of strip a and strip c (the matrix A);
+// otherwise out[next(i)][j] = (U_a^T T)[i][j] (the eigenvector rows Vt).  A block takes `ct` consecutive column
+// tiles of one strip: U_a stays in LDS, the next tile's T is on its way from memory into registers while the
+// current tile is multiplied, and the lanes' operand values of U_c for the second product are fetched (from L2:
+// every block of the column uses them) before the first product starts.  X = U_a^T T takes T's place in LDS, so
+// two blocks fit a compute unit and one multiplies while the other loads and stores.
+// Dynamic LDS: 2 matrices of 64 x 65 doubles.
+template <bool TWO_SIDED>
+__global__ __launch_bounds__(256, 2) void k_bjacobi_apply(const double *__restrict__ M, const double *__restrict__ Uall,
+                                                          int n, int ct, double *__restrict__ out)
+{
+    extern __shared__ double bj_smem[];
+    double *Ua = bj_smem, *T = Ua + BJ_S * BJ_LD;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lm = lane & 15, lq = lane >> 4, wm = wave >> 1, wn = wave & 1;
+    const int a = blockIdx.y, strips = n / BJ_S;
+    const int c_begin = blockIdx.x * ct, c_end = min(c_begin + ct, strips);
+    constexpr int PER = BJ_S * BJ_S / 256;
+    double rt[PER];
+    auto fetch = [&](int c) {
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int idx = tid + 256 * e, i = idx >> 6, j = idx & 63;
+            rt[e] = M[(size_t)(a * BJ_S + i) * n + c * BJ_S + j];
+        }
+    };
+    if (c_begin < c_end) fetch(c_begin);
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+        const int idx = tid + 256 * e;
+        Ua[(idx >> 6) * BJ_LD + (idx & 63)] = Uall[(size_t)a * BJ_S * BJ_S + idx];
+    }
+    for (int c = c_begin; c < c_end; ++c) {
+        __syncthreads();            // the previous tile's readers are done with T (holding X)
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const int idx = tid + 256 * e;
+            T[(idx >> 6) * BJ_LD + (idx & 63)] = rt[e];
+        }
+        __syncthreads();
+        if (c + 1 < c_end) fetch(c + 1);
+        double ub[BJ_S / 4][2];     // U_c[4 kk + lq][this lane's two columns]
+        if (TWO_SIDED) {
+#pragma unroll
+            for (int kk = 0; kk < BJ_S / 4; ++kk)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    ub[kk][j] = Uall[(size_t)c * BJ_S * BJ_S + (4 * kk + lq) * BJ_S + wn * 32 + j * 16 + lm];
+        }
+        f64x4_t acc[2][2];
+        bj_mma64<true>(Ua, T, wm, wn, lm, lq, acc);
+        if (TWO_SIDED) {
+            __syncthreads();        // every wave has read T
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        T[(wm * 32 + i * 16 + 4 * v + lq) * BJ_LD + wn * 32 + j * 16 + lm] = acc[i][j][v];
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kk = 0; kk < BJ_S / 4; ++kk) {
+                double fa[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) fa[i] = T[(wm * 32 + i * 16 + lm) * BJ_LD + 4 * kk + lq];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], ub[kk][j], acc[i][j], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = a * BJ_S + wm * 32 + i * 16 + 4 * v + lq;
+                    const int col = c * BJ_S + wn * 32 + j * 16 + lm;
+                    out[(size_t)bjacobi_next_index(row, n) * n + (TWO_SIDED ? bjacobi_next_index(col, n) : col)] =
+                        acc[i][j][v];
+                }
     }
 }
 
