@@ -702,8 +702,9 @@ def main():
                     "traffic": (tr or {}).get("rows_traffic_per_launch"),
                     "traffic_algorithmic_bytes_same_launches": (tr or {}).get("rows_algorithmic_per_launch"),
                     "frac_of_measured_ceiling": of_ceiling(ach_rows),
-                    "kernel": "k_rows (mask scan, gate/up/down over the active rows), launched alone K times from the "
-                              "steps' mask words (svdp_active_rows), HIP events around the replayed graph",
+                    "kernel": "k_rows (mask scan, gate/up/down over the active rows; for batches on the matrix cores the "
+                              "pair k_gate_up_mfma + k_down_slices), launched alone K times from the steps' mask words "
+                              "(svdp_active_rows), HIP events around the replayed graph",
                     "us_per_launch": r["us_rows"], "algorithmic_bytes_per_launch": r["bytes_rows"]}
     else:
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -176,10 +176,11 @@ svdp_status svdp_ffn_step_static(const svdp_layer *layer, const void *x, int32_t
 /* The sparse FFN of svdp_ffn_step from given mask words, without the predictor (Alg. 3 after its
  * first line): the row kernel scans the mask words, takes its share of the ascending list and
  * computes gate and up over the active rows; the down projection follows and y [B][d] is fully
- * written, bit for bit what svdp_ffn_step gives for the same mask.  With y == NULL only the row
- * kernel (the dominant one) is enqueued and its partial results stay in the workspace: that form
- * exists so that the kernel can be timed by itself.  mask: device [D/64] words as written by svdp_compact or
- * svdp_ffn_step.                                                                                  */
+ * written, bit for bit what svdp_ffn_step gives for the same mask.  With y == NULL everything but
+ * the final sum of the partial results is enqueued (the row kernel; for batches on the matrix
+ * cores the gate/up kernel and the down-projection kernel) and the partial results stay in the
+ * workspace: that form exists so that the dominant kernels can be timed by themselves.
+ * mask: device [D/64] words as written by svdp_compact or svdp_ffn_step.                        */
 svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, const uint64_t *mask,
                              float *y, void *ws, size_t ws_bytes, void *stream);
 

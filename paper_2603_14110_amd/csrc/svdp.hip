@@ -174,7 +174,20 @@ struct RowsPlan {
     int max_chunk;      // LDS row capacity of a block
     int min_chunk;      // fewest rows a block takes (short lists use fewer blocks)
     size_t lds;
+    bool split;         // gate/up kernel, then the down projection over column slices (k_down_slices)
 };
+
+// Split organisation: parts of the list per column slice, fewest rows of a part, and where its buffers lie
+// inside the workspace's partial-y region [ROWS_BLOCKS][NB][d]: the RG partial y's, then h [D][NB], then the list [D].
+constexpr int DOWN_RG = 8;
+constexpr int DOWN_MIN_CHUNK = 64;
+inline size_t split_h_offset(int d, int NB) { return align_up((size_t)DOWN_RG * NB * d * 4); }
+inline size_t split_list_offset(int d, int D, int NB) { return split_h_offset(d, NB) + align_up((size_t)D * NB * 4); }
+inline bool split_fits(int d, int D, int NB)
+{
+    return (D + DOWN_RG - 1) / DOWN_RG <= DS_MAX_CHUNK && d % DS_SW == 0 &&
+           split_list_offset(d, D, NB) + (size_t)D * 4 <= (size_t)ROWS_BLOCKS * NB * d * 4;
+}
 
 template <typename W, int NB>
 RowsPlan plan_rows(const svdp_layer *L)
@@ -182,6 +195,7 @@ RowsPlan plan_rows(const svdp_layer *L)
     const int d = L->d, D = L->D, G = ROWS_BLOCKS;
     const int per = (D + G - 1) / G;
     RowsPlan p;
+    p.split = false;
     if ((L->flags & SVDP_FLAG_REVALIDATE) != 0) {
         p.kind = ROWS_SEQ;
         p.min_chunk = 4;
@@ -197,9 +211,10 @@ RowsPlan plan_rows(const svdp_layer *L)
             p.kind = ROWS_MATRIX;
             p.min_chunk = MF_ROWS;
             p.max_chunk = round_up(per > p.min_chunk ? per : p.min_chunk, MF_ROWS);
-            p.lds = (size_t)NB * d * 2 +
-                    ((size_t)ROWS_WAVES * p.max_chunk * 2 * NB + (size_t)p.max_chunk * MF_TOK + p.max_chunk) * 4;
-            if (p.lds <= LDS_MAX) return p;
+            p.lds = (size_t)NB * d * 2 + ((size_t)ROWS_WAVES * p.max_chunk * 2 * NB + p.max_chunk) * 4;
+            p.split = true;
+            if (p.lds <= LDS_MAX && split_fits(d, D, NB)) return p;
+            p.split = false;
         }
     }
     p.kind = ROWS_VECTOR;
@@ -343,7 +358,7 @@ bool prepare_rows(const svdp_layer *L)
     const RowsPlan p = plan_rows<W, NB>(L);
     if (p.kind == ROWS_SEQ) return grant_lds<k_rows_seq<W, NB, MODE>>(p.lds);
     if constexpr (std::is_same<W, bf16>::value) {
-        if (p.kind == ROWS_MATRIX) return grant_lds<k_rows_mfma<NB, MODE>>(p.lds);
+        if (p.kind == ROWS_MATRIX) return grant_lds<k_gate_up_mfma<NB, MODE>>(p.lds);
     }
     return grant_lds<k_rows<W, NB, MODE>>(p.lds);
 }
@@ -366,9 +381,13 @@ svdp_status launch_rows_only(const svdp_layer *L, const void *x, int B, const ui
     }
     if constexpr (std::is_same<W, bf16>::value) {
         if (p.kind == ROWS_MATRIX) {
-            hipLaunchKernelGGL((k_rows_mfma<NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs,
-                               B, d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk,
-                               L->flags, w.ypart);
+            float *hbuf = reinterpret_cast<float *>(reinterpret_cast<char *>(w.ypart) + split_h_offset(d, NB));
+            int32_t *lst = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(w.ypart) + split_list_offset(d, D, NB));
+            hipLaunchKernelGGL((k_gate_up_mfma<NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, xs, B,
+                               d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags,
+                               hbuf, lst);
+            hipLaunchKernelGGL((k_down_slices<NB, MODE == ROWS_DENSE>), dim3(d / DS_SW, DOWN_RG), dim3(DS_THREADS), 0, st,
+                               Wd, lst, MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, d, hbuf, DOWN_MIN_CHUNK, w.ypart);
             return hip_status(hipSuccess);
         }
     }
@@ -388,7 +407,8 @@ svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_
     const int vpt = L->d / 4;
     const int blocks = B * ((vpt + RED_COLS - 1) / RED_COLS);
     hipLaunchKernelGGL(k_reduce_y, dim3(blocks), dim3(RED_COLS * RED_SEGS), 0, st, w.ypart,
-                       MODE == ROWS_DENSE ? nullptr : w.nnz, L->D, L->D, ROWS_BLOCKS, p.min_chunk, NB, B, L->d, y);
+                       MODE == ROWS_DENSE ? nullptr : w.nnz, L->D, L->D, p.split ? DOWN_RG : ROWS_BLOCKS,
+                       p.split ? DOWN_MIN_CHUNK : p.min_chunk, NB, B, L->d, y);
     return hip_status(hipSuccess);
 }
 

@@ -1,29 +1,21 @@
 // Kernels on the matrix cores.
 //
-// k_rows_mfma: gate, up and down over a list of rows, for batches of
-// several tokens in bf16 storage (the regime the paper's Sec. 6 names as the
-// limit of the sparse path: the union of the tokens' masks is dense enough that
-// a row-at-a-time kernel spends its time in per-token vector arithmetic, and
-// App. C's Alg. 4 treats the selected rows as a small dense contraction).
-// Same contract, list handling and partial-y layout as k_rows; only the
-// arithmetic differs:
-//   phase A: tiles of 16 list rows x 64 elements of d; four lanes fetch 64
-//            contiguous bytes of one row per load, two loads cover 128 bytes and
-//            feed two v_mfma_f32_16x16x32_bf16 per matrix, whose other operand
-//            is x in LDS, stored in operand order.  The eight waves of the block
-//            split d between them; their 16x16 partial tiles meet in LDS and are
-//            added in wave order, then h = ReLU(g)*u.
-//   phase B: y[token][col] += h[token][row] * W_downT[row][col] as fp32 outer
-//            products, v_mfma_f32_4x4x1_16b_f32: a wave's 16-byte-per-lane load
-//            is 1 KB of one row (512 columns); after widening to fp32 each of
-//            the eight columns of a lane goes through one instruction per group
-//            of four tokens, and h stays fp32.  A wave owns 512-column tiles and
-//            walks the chunk row by row, MF_UB rows in flight, the first of them
-//            requested before phase A's results are combined.
+// The FFN over a list of rows for batches of several tokens in bf16 storage (the regime the paper's
+// Sec. 6 names as the limit of the sparse path: the union of the tokens' masks is dense enough that a
+// row-at-a-time kernel spends its time in per-token vector arithmetic, and App. C's Alg. 4 treats the
+// selected rows as a small dense contraction), in two kernels:
+//   k_gate_up_mfma  same contract and list handling as k_rows, but it ends with h = ReLU(g) * u of its
+//            chunk of the list written to memory (h [list position][NB], and the checked list).  Tiles of 16
+//            list rows x 64 elements of d; four lanes fetch 64 contiguous bytes of one row per load, two
+//            loads cover 128 bytes and feed two v_mfma_f32_16x16x32_bf16 per matrix, whose other operand is
+//            x in LDS, stored in operand order.  The eight waves of the block split d between them; their
+//            16x16 partial tiles meet in LDS and are added in wave order.
+//   k_down_slices   y[token][col] = sum over the list of h * W_downT[row][col], by blocks that own a
+//            128-byte column slice and one of eight parts of the list (see there).
 // Products of bf16 values are exact in fp32 and every sum has a fixed order.
 // Requirements checked by the host: d % 512 == 0, NB <= 8.
-// Dynamic LDS: NB*d*2 bytes (x) + ROWS_WAVES*max_chunk*2*NB floats (partial
-// tiles) + max_chunk*16 floats (h) + max_chunk ints (list); max_chunk % 16 == 0.
+// Dynamic LDS of k_gate_up_mfma: NB*d*2 bytes (x) + ROWS_WAVES*max_chunk*2*NB floats (partial tiles) +
+// max_chunk ints (list); max_chunk % 16 == 0.
 #pragma once
 
 #include "svdp_kernels.h"
@@ -34,9 +26,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int MF_ROWS = 16;      // list rows per phase-A tile
 constexpr int MF_TOK = 16;       // token slots of a tile (slots >= NB are padding)
-constexpr int MF_UA = 4;         // phase A: 64-element steps fetched together
-constexpr int MF_UB = 8;         // phase B: rows fetched together
-constexpr int MF_COLS = 512;     // phase B: columns per wave tile (eight per lane)
+constexpr int MF_UA = 4;         // 64-element steps fetched together
 
 __device__ __forceinline__ f32x4_t mfma_bf16(const uint4 &a, const uint4 &b, f32x4_t c)
 {
@@ -45,12 +35,11 @@ __device__ __forceinline__ f32x4_t mfma_bf16(const uint4 &a, const uint4 &b, f32
 }
 
 template <int NB, int MODE>
-__global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
-    const bf16 *__restrict__ Wg, const bf16 *__restrict__ Wu, const bf16 *__restrict__ WdT,
-    const bf16 *__restrict__ x, int B, int d, int D, const uint64_t *__restrict__ mask,
-    const int32_t *__restrict__ idx_in, const int32_t *__restrict__ nnz_in, int32_t *__restrict__ idx_out,
-    int32_t *__restrict__ nnz_out, int32_t *__restrict__ n_used, int max_chunk, int min_chunk, uint32_t flags,
-    float *__restrict__ ypart)
+__global__ __launch_bounds__(ROWS_THREADS) void k_gate_up_mfma(
+    const bf16 *__restrict__ Wg, const bf16 *__restrict__ Wu, const bf16 *__restrict__ x, int B, int d, int D,
+    const uint64_t *__restrict__ mask, const int32_t *__restrict__ idx_in, const int32_t *__restrict__ nnz_in,
+    int32_t *__restrict__ idx_out, int32_t *__restrict__ nnz_out, int32_t *__restrict__ n_used, int max_chunk,
+    int min_chunk, uint32_t flags, float *__restrict__ hbuf, int32_t *__restrict__ lst)
 {
     static_assert(NB == 1 || NB == 2 || NB == 4 || NB == 8, "token slots are addressed with a mask");
     extern __shared__ uint4 smem16[];
@@ -58,8 +47,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
     const int nsteps = d / 64;                                     // phase-A steps per row
     uint4 *xs = smem16;                                            // [nsteps][2][4][NB], operand order
     float *part = reinterpret_cast<float *>(xs + NB * nvec);       // [ROWS_WAVES][tiles][2][16][NB]
-    float *hs = part + (size_t)ROWS_WAVES * max_chunk * 2 * NB;    // [max_chunk][MF_TOK]
-    int *lidx = reinterpret_cast<int *>(hs + (size_t)max_chunk * MF_TOK);
+    int *lidx = reinterpret_cast<int *>(part + (size_t)ROWS_WAVES * max_chunk * 2 * NB);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lm = lane & 15, lq = lane >> 4;
     const int G = gridDim.x;
@@ -94,6 +82,8 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
     rows_block_list<MODE>(D, mask, idx_in, lane_first, wpl, held, lo, hi, lidx);
     if (MODE == ROWS_MASK && idx_out != nullptr)
         for (int q = tid; q < cnt; q += ROWS_THREADS) idx_out[lo + q] = lidx[q];
+    if (MODE != ROWS_DENSE)
+        for (int q = tid; q < cnt; q += ROWS_THREADS) lst[lo + q] = lidx[q];
 
     const bool drelu = (flags & 1u) != 0;
     // rows past the end of the chunk repeat its last row, and a rejected entry of the caller's list
@@ -104,7 +94,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
     };
     const int ntile = (cnt + MF_ROWS - 1) / MF_ROWS;
 
-    // ---- phase A: this wave's share of d is the steps [wave*spw, (wave+1)*spw) ----
+    // ---- this wave's share of d is the steps [wave*spw, (wave+1)*spw) ----
     const int spw = nsteps / ROWS_WAVES;
     const int tb = lm & (NB - 1);                                   // token slot read as the x operand
     for (int t = 0; t < ntile; ++t) {
@@ -146,28 +136,12 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
             }
         }
     }
-    // ---- phase B's first loads, requested before the waves meet.  A unit is one row of the
-    // chunk over one 512-column tile (tiles wave, wave + ROWS_WAVES, ...) ----
-    const int nct = d / MF_COLS;
-    const int nu = ((nct - wave + ROWS_WAVES - 1) / ROWS_WAVES) * cnt;    // units of this wave
-    auto unit_ptr = [&](int j, int q) -> const bf16 * {
-        return WdT + row_of(q) * d + (size_t)(wave + j * ROWS_WAVES) * MF_COLS + (size_t)lane * 8;
-    };
-    int ji = 0, qi = 0;                                             // next unit to request
-    uint4 cur[MF_UB];
-#pragma unroll
-    for (int k = 0; k < MF_UB; ++k) {
-        if (k < nu) {
-            cur[k] = load_raw(unit_ptr(ji, qi));
-            if (++qi == cnt) { qi = 0; ++ji; }
-        }
-    }
     __syncthreads();
-    // partial tiles of the waves, added in wave order -> h[row][token slot]
-    for (int e = tid; e < ntile * MF_ROWS * MF_TOK; e += ROWS_THREADS) {
-        const int q = e / MF_TOK, b = e % MF_TOK;
+    // partial tiles of the waves, added in wave order -> h[list position][token]
+    for (int e = tid; e < cnt * NB; e += ROWS_THREADS) {
+        const int q = e / NB, b = e % NB;
         float h = 0.f;
-        if (b < NB && q < cnt && (MODE != ROWS_LIST || lidx[q] >= 0)) {
+        if (MODE != ROWS_LIST || lidx[q] >= 0) {
             const int t = q / MF_ROWS, rr = q % MF_ROWS;
             float gs = 0.f, us = 0.f;
 #pragma unroll
@@ -178,72 +152,133 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_rows_mfma(
             }
             h = fmaxf(gs, 0.f) * (drelu ? fmaxf(us, 0.f) : us);
         }
-        hs[e] = h;
+        hbuf[(size_t)(lo + q) * NB + b] = h;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Down projection over column slices, for batches (Alg. 4's last product; App. C: W_down is stored by columns,
+// W_downT [D][d], so that a selected neuron is one contiguous row):
+//     y[token][col] = sum over the list of h[position][token] * W_downT[row(position)][col].
+// Block (slice, rg) owns the 64 columns (one 128-byte line of every row) [64 slice, +64) and the rg-th of RG equal
+// parts of the list, and writes its sums to ypart [rg][NB][d]; k_reduce_y adds the RG parts.  Against one partial
+// y per row-kernel block (256 of them: 32 MB written and read again at eight tokens) this leaves RG * NB * d
+// floats.  Eight lanes fetch the 128 bytes of a row, so a wave's load instruction covers eight rows; a lane keeps
+// NB x 8 sums (its eight columns for every token), and h (written by the gate/up kernel, a few hundred KB that stay
+// in L2) is read by position.  The sums over a wave's eight row lanes and then over the waves are taken in a fixed
+// order through LDS.
+// Requirements checked by the host: d a multiple of the slice width, ceil(D / RG) <= DS_MAX_CHUNK.
+// ---------------------------------------------------------------------------
+constexpr int DS_THREADS = 256;
+constexpr int DS_WAVES = DS_THREADS / 64;
+constexpr int DS_UB = 4;             // wave loads (eight rows each) in flight, twice while the next group is fetched
+constexpr int DS_MAX_CHUNK = 4096;   // list entries of a block kept in LDS
+constexpr int DS_LPR = 8;            // lanes per row: 16 bytes each, one 128-byte line
+constexpr int DS_SW = DS_LPR * 8;    // columns of a slice
+
+template <int NB, bool DENSE>
+__global__ __launch_bounds__(DS_THREADS) void k_down_slices(const bf16 *__restrict__ WdT,
+                                                            const int32_t *__restrict__ lst,
+                                                            const int32_t *__restrict__ n_ptr, int n_fixed, int D, int d,
+                                                            const float *__restrict__ hbuf, int min_chunk,
+                                                            float *__restrict__ ypart)
+{
+    constexpr int LPR = DS_LPR, SW = DS_SW;
+    constexpr int RPW = 64 / LPR;                // rows per wave load
+    constexpr int RSETS = RPW / 2;               // row-lane sets of a wave left after the lane shift below
+    __shared__ int lidx[DENSE ? 1 : DS_MAX_CHUNK];
+    __shared__ float red[DS_WAVES * RSETS * NB * SW];         // [DS_WAVES * RSETS][NB][SW]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cg = lane % LPR, sub = lane / LPR;
+    const int slice = blockIdx.x, rg = blockIdx.y, RG = gridDim.y;
+    int n = n_ptr != nullptr ? *n_ptr : n_fixed;
+    n = max(0, min(n, D));
+    const int chunk = chunk_of(n, RG, min_chunk);
+    const int lo = min(n, rg * chunk), hi = min(n, lo + chunk), cnt = hi - lo;
+    if (cnt <= 0) return;
+    if (!DENSE) {
+        for (int q = tid; q < cnt; q += DS_THREADS) lidx[q] = lst[lo + q];
+        __syncthreads();
+    }
+    const bf16 *colp = WdT + (size_t)slice * SW + (size_t)cg * 8;
+    const int ngroups = (cnt + RPW - 1) / RPW;
+
+    // v_mfma_f32_4x4x1_16b: sixteen independent 4 x 4 outer products; the four lanes of a block work on the same
+    // row, lane j of the block supplies h of token 4 tg + j and its own column's weight, and keeps the four tokens'
+    // sums for its own column: acc[tg][e][i] belongs to token 4 tg + i and column 8 cg + e.
+    constexpr int TG = (NB + 3) / 4;
+    f32x4_t acc[TG][8];
+#pragma unroll
+    for (int g = 0; g < TG; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // group g of the chunk = its rows RPW g .. RPW g + RPW - 1; this wave takes the groups wave, wave + DS_WAVES, ...
+    auto fetch = [&](int g0, uint4 (&wv)[DS_UB], float (&hv)[DS_UB][TG]) {
+#pragma unroll
+        for (int k = 0; k < DS_UB; ++k) {
+            const int q = (g0 + k * DS_WAVES) * RPW + sub;
+            wv[k] = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int g = 0; g < TG; ++g) hv[k][g] = 0.f;
+            if (q < cnt) {
+                const int row = DENSE ? lo + q : lidx[q];
+                if (row >= 0) {                                    // a rejected entry of the caller's list: h is zero
+                    wv[k] = load_raw(colp + (size_t)row * d);
+                    const float *hp = hbuf + (size_t)(lo + q) * NB;
+#pragma unroll
+                    for (int g = 0; g < TG; ++g)
+                        if (g * 4 + (lane & 3) < NB) hv[k][g] = hp[g * 4 + (lane & 3)];
+                }
+            }
+        }
+    };
+    auto consume = [&](const uint4 (&wv)[DS_UB], const float (&hv)[DS_UB][TG]) {
+#pragma unroll
+        for (int k = 0; k < DS_UB; ++k) {
+            float w[8];
+            widen(wv[k], w, (const bf16 *)nullptr);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int g = 0; g < TG; ++g)
+                    acc[g][e] = __builtin_amdgcn_mfma_f32_4x4x1f32(hv[k][g], w[e], acc[g][e], 0, 0, 0);
+        }
+    };
+    {
+        uint4 wa[DS_UB], wb[DS_UB];
+        float ha[DS_UB][TG], hb[DS_UB][TG];
+        constexpr int STEP = DS_WAVES * DS_UB;
+        fetch(wave, wa, ha);
+        for (int g0 = wave; g0 < ngroups; g0 += 2 * STEP) {
+            fetch(g0 + STEP, wb, hb);            // past the end: nothing is requested
+            consume(wa, ha);
+            fetch(g0 + 2 * STEP, wa, ha);
+            consume(wb, hb);
+        }
+    }
+    // row lanes l and l ^ 8 first (a lane shift), then the four remaining sets of a wave and the waves through
+    // LDS, in order
+#pragma unroll
+    for (int g = 0; g < TG; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[g][e][i] += dpp_move<0x128>(acc[g][e][i]);           // row_ror:8
+    if ((sub & 1) == 0) {
+        const int set = wave * RSETS + (sub >> 1);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[(set * NB + b) * SW + cg * 8 + e] = acc[b / 4][e][b % 4];
     }
     __syncthreads();
-
-    // ---- phase B: the wave's units are walked in one sequence, MF_UB of them fetched ahead, so
-    // that the loads of the next column tile are in flight while the current one is finished.
-    // v_mfma_f32_4x4x1_16b: sixteen independent 4x4 outer products; block l/4 of lane l gets
-    // (h of four tokens for this row) x (the lane's and its three neighbours' weights), and the
-    // lane keeps the four tokens' sums for its own column ----
-    {
-        constexpr int TG = (NB + 3) / 4;                            // groups of four tokens
-        f32x4_t acc[TG][8];
+    for (int o = tid; o < NB * SW; o += DS_THREADS) {
+        const int b = o / SW, c = o % SW;
+        float t = 0.f;
 #pragma unroll
-        for (int g = 0; g < TG; ++g)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[g][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        int jc = 0, qc = 0;                                         // unit being computed
-        for (int base = 0; base < nu; base += MF_UB) {
-            uint4 nxt[MF_UB];
-#pragma unroll
-            for (int k = 0; k < MF_UB; ++k) {
-                if (base + MF_UB + k < nu) {
-                    nxt[k] = load_raw(unit_ptr(ji, qi));
-                    if (++qi == cnt) { qi = 0; ++ji; }
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < MF_UB; ++k) {
-                if (base + k < nu) {
-                    float a[TG];
-#pragma unroll
-                    for (int g = 0; g < TG; ++g) a[g] = hs[qc * MF_TOK + g * 4 + (lane & 3)];
-                    float w[8];
-                    widen(cur[k], w, (const bf16 *)nullptr);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-#pragma unroll
-                        for (int g = 0; g < TG; ++g)
-                            acc[g][e] = __builtin_amdgcn_mfma_f32_4x4x1f32(a[g], w[e], acc[g][e], 0, 0, 0);
-                    if (++qc == cnt) {
-                        // register i of a group holds token 4g+i for columns ct*512 + lane*8 + e
-                        const int ct = wave + jc * ROWS_WAVES;
-#pragma unroll
-                        for (int g = 0; g < TG; ++g)
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int b = g * 4 + i;
-                                if (b < NB) {
-                                    float4 *out = reinterpret_cast<float4 *>(ypart + ((size_t)blockIdx.x * NB + b) * d +
-                                                                             (size_t)ct * MF_COLS + (size_t)lane * 8);
-                                    out[0] = make_float4(acc[g][0][i], acc[g][1][i], acc[g][2][i], acc[g][3][i]);
-                                    out[1] = make_float4(acc[g][4][i], acc[g][5][i], acc[g][6][i], acc[g][7][i]);
-                                }
-                            }
-#pragma unroll
-                        for (int g = 0; g < TG; ++g)
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) acc[g][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                        qc = 0;
-                        ++jc;
-                    }
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < MF_UB; ++k) cur[k] = nxt[k];
-        }
+        for (int p = 0; p < DS_WAVES * RSETS; ++p) t += red[(p * NB + b) * SW + c];
+        ypart[((size_t)rg * NB + b) * d + (size_t)slice * SW + c] = t;
     }
 }
 
