@@ -406,6 +406,7 @@ def run_stack(a, torch, np, binding, cost, synth):
     return res
 
 
+TRAFFIC_PROFILE_MISTRAL_B8 = "profiles/ffn_step_mistral_b8_pmc_traffic.txt"
 TRAFFIC_PROFILE = os.path.join("profiles", "ffn_step_7b_pmc_traffic.txt")
 
 
@@ -414,14 +415,22 @@ def measured_traffic(a):
     WRITE_SIZE runs of `bench.py --traffic-pass`, calibrated on a plain copy of known size) - but only when
     that summary holds an entry for exactly this run's timed sample (workload, number of steps, sampling seed);
     otherwise None, and the line carries no traffic figure."""
-    if not (a.workload == "7b" and a.batch == 1 and a.rank in (0, 256) and (a.flags & 3) == 0 and a.engine == "auto"):
+    if (a.flags & 3) != 0 or a.engine != "auto" or a.rank not in (0, 256):
+        return None
+    if a.workload == "7b" and a.batch == 1:
+        profile = TRAFFIC_PROFILE
+    elif a.workload == "mistral" and a.batch == 8:
+        profile = TRAFFIC_PROFILE_MISTRAL_B8
+    else:
         return None
     try:
-        for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
+        for line in open(os.path.join(ROOT, profile)):
             if line.startswith("entry "):
                 e = dict(kv.split("=") for kv in line.split()[1:])
                 if int(e["steps"]) == a.steps and int(e["sample_seed"]) == SAMPLE_SEED:
-                    return {k: float(v) for k, v in e.items()}
+                    out = {k: float(v) for k, v in e.items()}
+                    out["source"] = profile
+                    return out
     except (OSError, ValueError, KeyError):
         pass
     return None
@@ -748,11 +757,11 @@ def main():
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": (tr or {}).get("step_traffic"),
             "traffic_algorithmic_bytes_same_steps": (tr or {}).get("step_algorithmic"),
-            "traffic_source": (TRAFFIC_PROFILE + " (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of `bench.py --traffic-pass` "
+            "traffic_source": (tr["source"] + " (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of `bench.py --traffic-pass` "
                                "on this run's timed sample)") if tr else None,
             "frac_of_measured_ceiling": of_ceiling(achieved),
-            "kernel": "whole step: all kernels svdp_ffn_step launches (k_xP, k_scores, k_rows, k_reduce_y), "
-                      "timed together with HIP events around the replayed graph",
+            "kernel": "whole step: all kernels svdp_ffn_step launches (k_xP, k_scores, k_rows or k_gate_up_mfma + "
+                      "k_down_slices, k_reduce_y), timed together with HIP events around the replayed graph",
             "algorithmic_bytes_per_step": r["bytes_step"],
         },
         "machine_floor": floor,
