@@ -238,16 +238,17 @@ svdp_status svdp_calib_bias(const float *w, const float *s, int32_t D, int32_t T
  * the rank-r pair A = U_r Sigma_r, B = V_r^T S^-1 minimises ||(W_gate - A B) X^T||_F over rank-r products.
  * Outputs in the library's letters, fp32, device: Q = A [D][r], P = B^T [d][r], so that the predictor's
  * scores are (x P) Q^T; the caller rounds them to the layer's storage type.  sigma [r] (host, nullable):
- * the r leading singular values of W_gate S, descending.  sweeps [2] (host, nullable): Jacobi sweeps the
- * two eigen-decompositions took.
- * The product A B does not depend on which factor S is taken (Alg. 1 prints the Cholesky factor); here
- * S = E Lambda^1/2 from the symmetric eigen-decomposition X^T X = E Lambda E^T, so that one eigen-solver
- * serves both factorisations and S^-1 = Lambda^-1/2 E^T needs no triangular solve.  All arithmetic is
- * fp64: contractions on the matrix cores, the two d x d eigen-decompositions by cyclic Jacobi sweeps.
- * Needs d a multiple of 64, T >= d and X^T X positive definite (smallest eigenvalue > 1e-12 of the
- * largest), r <= d; otherwise SVDP_ERR_UNSUPPORTED.
+ * the r leading singular values of W_gate S, descending.  sweeps [2] (host, nullable): sweeps[0] = 0,
+ * sweeps[1] = block-Jacobi sweeps the eigen-decomposition took.
+ * S is the lower Cholesky factor of X^T X, as Alg. 1 prints it (blocked factorisation, 64-wide blocks);
+ * V and Sigma^2 come from the symmetric eigen-decomposition of (W_gate S)^T (W_gate S) by block Jacobi
+ * sweeps, and S^-1 is applied to the r chosen vectors by block back-substitution.  All arithmetic is
+ * fp64, the contractions on the matrix cores.
+ * Needs d a multiple of 64, T >= d and X^T X positive definite to working precision (every pivot of
+ * the factorisation above 1e-13 of the largest diagonal element), r <= d; otherwise
+ * SVDP_ERR_UNSUPPORTED.
  * Unlike the decode calls this one is an offline step: it SYNCHRONISES `stream` several times (it reads
- * convergence figures and eigenvalues on the host) and cannot be captured in a graph.  It allocates
+ * the factorisation's verdict, convergence figures and eigenvalues on the host) and cannot be captured in a graph.  It allocates
  * nothing on the device.  ws: device, 256-byte aligned, >= svdp_whiten_workspace_bytes(d, D, T, r)
  * (0 for sizes it does not take).                                                                      */
 size_t svdp_whiten_workspace_bytes(int32_t d, int32_t D, int32_t T, int32_t r);

@@ -489,9 +489,11 @@ struct WhitenWs {
     double *Xt;                 // [d][T]
     double *A0, *A1;            // [d][d] symmetric matrix, ping-pong
     double *V0, *V1;            // [d][d] eigenvectors as rows, ping-pong
-    double *St;                 // [d][d]  S^T = sqrt(lambda) * E^T
-    double *E;                  // [d][d]  E (eigenvectors of X^T X as columns)
-    double *lamC, *lamG;        // [d] eigenvalues by place
+    double *St;                 // [d][d]  S^T, S = the lower Cholesky factor of X^T X
+    double *E;                  // [d][d]  S
+    double *lamG;               // [d] eigenvalues by place
+    double *invL, *invLt;       // [64][64] scratch; [d/64][64][64] transposed inverses of S's diagonal blocks
+    int32_t *fail;              // set by the factorisation if X^T X is not positive definite
     double *Vr;                 // [r][d]
     double *out64;              // [max(D, d)][r]
     double *Uall, *rowsums, *sums;     // [d/64][64][64] strip transforms; norms
@@ -520,8 +522,10 @@ WhitenWs carve_whiten(void *base, int d, int D, int T, int r)
     w.V1 = take(dd);
     w.St = take(dd);
     w.E = take(dd);
-    w.lamC = take(d);
     w.lamG = take(d);
+    w.invL = take(64 * 64);
+    w.invLt = take((size_t)d * 64);
+    w.fail = reinterpret_cast<int32_t *>(take(32));
     w.Vr = take((size_t)r * d);
     w.out64 = take((size_t)(D > d ? D : d) * r);
     w.Uall = take((size_t)d * 64);
@@ -535,10 +539,49 @@ WhitenWs carve_whiten(void *base, int d, int D, int T, int r)
 
 inline dim3 grid1(size_t n) { return dim3((unsigned)((n + 255) / 256)); }
 
-void dgemm_nt(const double *A, int lda, const double *Bm, int ldb, double *C, int ldc, int M, int N, int K, hipStream_t st)
+// C = A B^T, or with Cin: C = Cin - A B^T (C and Cin different memory)
+void dgemm_nt(const double *A, int lda, const double *Bm, int ldb, double *C, int ldc, int M, int N, int K, hipStream_t st,
+              const double *Cin = nullptr, int ldcin = 0)
 {
+    if (M <= 0 || N <= 0) return;
     hipLaunchKernelGGL(k_dgemm_nt, dim3((N + DG_BN - 1) / DG_BN, (M + DG_BM - 1) / DG_BM), dim3(256), 0, st, A, lda, Bm, ldb,
-                       C, ldc, M, N, K);
+                       C, ldc, M, N, K, Cin, ldcin);
+}
+
+// L (lower, [n][n], zero above the diagonal) with L L^T = C; T: scratch [n][n]; invLt: [n/64][64][64], the
+// transposed inverses of L's diagonal blocks; invL: scratch [64][64]; scale: device double; fail: device int,
+// set to 1 if C is not positive definite to working precision (then L is not to be used).
+void cholesky_blocked(const double *C, double *L, double *T, int n, double *invL, double *invLt, double *scale, int *fail,
+                      hipStream_t st)
+{
+    const int nb = n / CH_B;
+    hipLaunchKernelGGL(k_max_diag, dim3(1), dim3(256), 0, st, C, n, scale);
+    for (int k = 0; k < nb; ++k) {
+        const size_t row0 = (size_t)k * CH_B * n, diag = row0 + (size_t)k * CH_B;
+        // T[k:, k] = C[k:, k] - L[k:, :k] L[k, :k]^T   (K = 0 for the first block column: a copy)
+        dgemm_nt(L + row0, n, L + row0, n, T + diag, n, n - k * CH_B, CH_B, k * CH_B, st, C + diag, n);
+        hipLaunchKernelGGL(k_chol_diag, dim3(1), dim3(256), 0, st, T, L, n, diag, scale, 1e-13, invL,
+                           invLt + (size_t)k * CH_B * CH_B, fail);
+        // L[k+1:, k] = T[k+1:, k] Lkk^-T
+        dgemm_nt(T + diag + (size_t)CH_B * n, n, invL, CH_B, L + diag + (size_t)CH_B * n, n, n - (k + 1) * CH_B, CH_B, CH_B,
+                 st);
+    }
+    hipLaunchKernelGGL(k_zero_upper_blocks, grid1((size_t)n * n), dim3(256), 0, st, L, n);
+}
+
+// Bout [r][n] = Bin [r][n] L^-1 for the lower-triangular L given as Lt = L^T [n][n] and the transposed inverses of
+// its diagonal blocks: block back-substitution from the last block column to the first.  tmp: scratch [r][64].
+void solve_right_lower(const double *Bin, double *Bout, int r, int n, const double *Lt, const double *invLt, double *tmp,
+                       hipStream_t st)
+{
+    const int nb = n / CH_B;
+    for (int i = nb - 1; i >= 0; --i) {
+        const int c0 = i * CH_B, rest = n - (i + 1) * CH_B;
+        // tmp = Bin[:, i] - Bout[:, i+1:] L[i+1:, i]      (L[k][c0 + a] = Lt[c0 + a][k])
+        dgemm_nt(Bout + c0 + CH_B, n, Lt + (size_t)c0 * n + c0 + CH_B, n, tmp, CH_B, r, CH_B, rest, st, Bin + c0, n);
+        // Bout[:, i] = tmp Lii^-1
+        dgemm_nt(tmp, CH_B, invLt + (size_t)i * CH_B * CH_B, CH_B, Bout + c0, n, r, CH_B, CH_B, st);
+    }
 }
 
 // Eigen-decomposition of the symmetric matrix in *A (n x n, n % 64 == 0) by block Jacobi sweeps.  On return
@@ -589,32 +632,32 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
     std::vector<double> lam(d);
     std::vector<int32_t> order(d);
 
-    // second moments C = X^T X  (d x d)
+    // second moments C = X^T X  (d x d) and its Cholesky factor S (lower, S S^T = C)
     hipLaunchKernelGGL((k_transpose_to_f64<W>), dim3((d + 31) / 32, (T + 31) / 32), dim3(256), 0, st, Xs, T, d, w.Xt);
-    double *A = w.A0, *Aalt = w.A1, *V = w.V0, *Valt = w.V1;
-    dgemm_nt(w.Xt, T, w.Xt, T, A, d, d, d, T, st);
-    int sw1 = 0, sw2 = 0;
-    svdp_status e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.Uall, w.rowsums, w.sums, w.lamC, tol, max_sweeps, &sw1, st);
-    if (e != SVDP_OK) return e;
-    if (hipMemcpyAsync(lam.data(), w.lamC, (size_t)d * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+    dgemm_nt(w.Xt, T, w.Xt, T, w.A0, d, d, d, T, st);
+    if (hipMemsetAsync(w.fail, 0, 4, st) != hipSuccess) {
+        (void)hipGetLastError();
+        return SVDP_ERR_HIP;
+    }
+    cholesky_blocked(w.A0, w.E, w.A1, d, w.invL, w.invLt, w.sums, w.fail, st);
+    int32_t failed = 0;
+    if (hipMemcpyAsync(&failed, w.fail, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) {
         (void)hipGetLastError();
         return SVDP_ERR_HIP;
     }
-    // S S^T = C needs C positive definite (more independent tokens than dimensions)
-    const double lmax = *std::max_element(lam.begin(), lam.end()), lmin = *std::min_element(lam.begin(), lam.end());
-    if (!(lmax > 0.0) || !(lmin > 1e-12 * lmax)) return SVDP_ERR_UNSUPPORTED;
-    // S = E sqrt(Lambda): S^T = rows of E^T scaled; E itself for P at the end
-    hipLaunchKernelGGL(k_scale_rows<1>, grid1((size_t)d * d), dim3(256), 0, st, V, w.lamC, d, d, w.St);
-    hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (d + 31) / 32), dim3(256), 0, st, V, d, d, w.E);
+    // S needs C positive definite (more independent tokens than dimensions)
+    if (failed != 0) return SVDP_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (d + 31) / 32), dim3(256), 0, st, w.E, d, d, w.St);
 
     // M = W_gate S, G = M^T M
     hipLaunchKernelGGL((k_to_f64<W>), grid1((size_t)D * d), dim3(256), 0, st, Wg, (size_t)D * d, w.W64);
     dgemm_nt(w.W64, d, w.St, d, w.M, d, D, d, d, st);
     hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (D + 31) / 32), dim3(256), 0, st, w.M, D, d, w.Mt);
-    A = w.A0; Aalt = w.A1; V = w.V0; Valt = w.V1;
+    double *A = w.A0, *Aalt = w.A1, *V = w.V0, *Valt = w.V1;
     dgemm_nt(w.Mt, D, w.Mt, D, A, d, d, d, D, st);
-    e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.Uall, w.rowsums, w.sums, w.lamG, tol, max_sweeps, &sw2, st);
+    int sw2 = 0;
+    svdp_status e = jacobi_eigh(&A, &Aalt, &V, &Valt, d, w.Uall, w.rowsums, w.sums, w.lamG, tol, max_sweeps, &sw2, st);
     if (e != SVDP_OK) return e;
     if (hipMemcpyAsync(lam.data(), w.lamG, (size_t)d * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) {
@@ -632,10 +675,10 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
     hipLaunchKernelGGL(k_gather_rows, grid1((size_t)r * d), dim3(256), 0, st, V, w.sel, r, d, nullptr, w.Vr);
     dgemm_nt(w.M, d, w.Vr, d, w.out64, r, D, r, d, st);
     hipLaunchKernelGGL(k_f64_to_f32, grid1((size_t)D * r), dim3(256), 0, st, w.out64, (size_t)D * r, Q);
-    // P = B^T = S^-T V_r = E Lambda^-1/2 V_r
-    hipLaunchKernelGGL(k_gather_rows, grid1((size_t)r * d), dim3(256), 0, st, V, w.sel, r, d, w.lamC, w.Vr);
-    dgemm_nt(w.E, d, w.Vr, d, w.out64, r, d, r, d, st);
-    hipLaunchKernelGGL(k_f64_to_f32, grid1((size_t)d * r), dim3(256), 0, st, w.out64, (size_t)d * r, P);
+    // B = V_r^T S^-1 (block back-substitution; V_r^T is w.Vr, rows = the chosen eigenvectors), P = B^T
+    solve_right_lower(w.Vr, w.out64, r, d, w.St, w.invLt, w.Uall, st);
+    hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (r + 31) / 32), dim3(256), 0, st, w.out64, r, d, w.M);
+    hipLaunchKernelGGL(k_f64_to_f32, grid1((size_t)d * r), dim3(256), 0, st, w.M, (size_t)d * r, P);
     if (hipStreamSynchronize(st) != hipSuccess) {                 // order[] leaves scope: the copy above must be done
         (void)hipGetLastError();
         return SVDP_ERR_HIP;
@@ -643,7 +686,7 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
     if (sigma != nullptr)
         for (int k = 0; k < r; ++k) sigma[k] = (float)std::sqrt(std::max(lam[order[k]], 0.0));
     if (sweeps != nullptr) {
-        sweeps[0] = sw1;
+        sweeps[0] = 0;              // the factor of the second moments is a Cholesky factor: no sweeps
         sweeps[1] = sw2;
     }
     return hip_status(hipSuccess);

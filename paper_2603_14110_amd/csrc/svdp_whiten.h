@@ -5,9 +5,10 @@
 // W_gate S = U Sigma V^T, and returns A = U_r Sigma_r, B = V_r^T S^-1, the rank-r pair
 // minimising ||(W_gate - A B) X^T||_F.  In the library's letters Q = A [D][r], P = B^T [d][r].
 //
-// Everything that is a dense contraction runs on the matrix cores (k_dgemm_nt, fp64 MFMA);
-// the two symmetric d x d eigen-decompositions (of X^T X, and of (W S)^T (W S), whose
-// eigenvectors are V and eigenvalues Sigma^2) are a two-sided BLOCK Jacobi method in which a round
+// Everything that is a dense contraction runs on the matrix cores (k_dgemm_nt, fp64 MFMA),
+// including the bulk of the blocked Cholesky factorisation that gives S and of the block
+// back-substitution that applies S^-1; the symmetric d x d eigen-decomposition (of (W S)^T (W S), whose
+// eigenvectors are V and eigenvalues Sigma^2) is a two-sided BLOCK Jacobi method in which a round
 // is ONE pass over the matrix: the blocks of rows and columns that are transformed together are
 // neighbours in memory, so a 64 x 64 tile needs only its own elements and the two small orthogonal
 // matrices of its row strip and column strip (products on the matrix cores), and the tile is
@@ -49,17 +50,6 @@ __global__ __launch_bounds__(256) void k_transpose_to_f64(const T *__restrict__ 
         if (c0 + y < cols && r0 + tx < rows) dst[(size_t)(c0 + y) * rows + r0 + tx] = tile[tx][y];
 }
 
-// dst[i][j] = src[i][j] * f(scale[i]) for a [rows][cols] fp64 matrix; POW = 1: sqrt, -1: 1/sqrt
-template <int POW>
-__global__ __launch_bounds__(256) void k_scale_rows(const double *__restrict__ src, const double *__restrict__ scale,
-                                                    int rows, int cols, double *__restrict__ dst)
-{
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (size_t)rows * cols) return;
-    const double s = sqrt(scale[i / cols]);
-    dst[i] = POW > 0 ? src[i] * s : src[i] / s;
-}
-
 // dst[k][j] = src[idx[k]][j] * (colscale ? 1/sqrt(colscale[j]) : 1) for k < nsel
 __global__ __launch_bounds__(256) void k_gather_rows(const double *__restrict__ src, const int32_t *__restrict__ idx,
                                                      int nsel, int cols, const double *__restrict__ colscale,
@@ -89,8 +79,10 @@ __global__ __launch_bounds__(256) void k_f64_to_f32(const double *__restrict__ s
 constexpr int DG_BM = 64, DG_BN = 64, DG_BK = 16;
 constexpr int DG_LD = DG_BK + 1;            // LDS row stride in doubles (odd: spreads the banks)
 
+// With Cin the result is Cin - A B^T (Cin [M][ldcin], not the same memory as C).
 __global__ __launch_bounds__(256) void k_dgemm_nt(const double *__restrict__ A, int lda, const double *__restrict__ Bm,
-                                                  int ldb, double *__restrict__ C, int ldc, int M, int N, int K)
+                                                  int ldb, double *__restrict__ C, int ldc, int M, int N, int K,
+                                                  const double *__restrict__ Cin, int ldcin)
 {
     __shared__ double sA[DG_BM * DG_LD];
     __shared__ double sB[DG_BN * DG_LD];
@@ -148,8 +140,96 @@ __global__ __launch_bounds__(256) void k_dgemm_nt(const double *__restrict__ A, 
             for (int v = 0; v < 4; ++v) {
                 const int m = m0 + wm * 32 + i * 16 + 4 * v + lq;
                 const int n = n0 + wn * 32 + j * 16 + lm;
-                if (m < M && n < N) C[(size_t)m * ldc + n] = acc[i][j][v];
+                if (m < M && n < N)
+                    C[(size_t)m * ldc + n] = Cin != nullptr ? Cin[(size_t)m * ldcin + n] - acc[i][j][v] : acc[i][j][v];
             }
+}
+
+// ---------------------------------------------------------------------------
+// Blocked Cholesky factorisation C = L L^T (Alg. 1's S), block size 64, left-looking.  Per block column k:
+//   T[k:, k] = C[k:, k] - L[k:, :k] L[k, :k]^T         k_dgemm_nt with Cin (T is a scratch matrix)
+//   L[k, k]  = chol(T[k, k]), and its inverse           k_chol_diag (one block, in LDS)
+//   L[k+1:, k] = T[k+1:, k] L[k, k]^-T                  k_dgemm_nt against the inverse
+// The inverses of the diagonal blocks are kept (transposed) for the block back-substitution that applies
+// L^-1 to the chosen singular vectors at the end.
+// ---------------------------------------------------------------------------
+constexpr int CH_B = 64;
+
+// out[0] = largest diagonal element of A [n][n] (one block)
+__global__ __launch_bounds__(256) void k_max_diag(const double *__restrict__ A, int n, double *__restrict__ out)
+{
+    __shared__ double sm[256];
+    double m = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) m = fmax(m, A[(size_t)i * n + i]);
+    sm[threadIdx.x] = m;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (threadIdx.x < w) sm[threadIdx.x] = fmax(sm[threadIdx.x], sm[threadIdx.x + w]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = sm[0];
+}
+
+// Lkk (lower, the part above the diagonal zero) = Cholesky factor of the 64 x 64 block at T + toff (row stride n),
+// written to L + toff; invL [64][64] = Lkk^-1 and invLt its transpose.  A pivot that is not above tiny * scale[0]
+// (the matrix is not positive definite to working precision) sets fail[0] = 1 and is replaced by that bound, so
+// that the rest of the run stays finite.
+__global__ __launch_bounds__(256) void k_chol_diag(const double *__restrict__ T, double *__restrict__ L, int n,
+                                                   size_t toff, const double *__restrict__ scale, double tiny,
+                                                   double *__restrict__ invL, double *__restrict__ invLt,
+                                                   int *__restrict__ fail)
+{
+    __shared__ double S[CH_B][CH_B + 1], X[CH_B][CH_B + 1];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < CH_B * CH_B; e += 256) S[e >> 6][e & 63] = T[toff + (size_t)(e >> 6) * n + (e & 63)];
+    const double bound = tiny * scale[0];
+    __syncthreads();
+    for (int j = 0; j < CH_B; ++j) {
+        if (tid == 0) {
+            double p = S[j][j];
+            if (!(p > bound)) {
+                fail[0] = 1;
+                p = bound > 0.0 ? bound : 1.0;
+            }
+            S[j][j] = sqrt(p);
+        }
+        __syncthreads();
+        if (tid > j && tid < CH_B) S[tid][j] /= S[j][j];
+        __syncthreads();
+        for (int e = tid; e < CH_B * CH_B; e += 256) {
+            const int i = e >> 6, c = e & 63;
+            if (c > j && i >= c) S[i][c] -= S[i][j] * S[c][j];
+        }
+        __syncthreads();
+    }
+    if (tid < CH_B) {                         // column tid of the inverse, by forward substitution
+        const int c = tid;
+        for (int i = 0; i < CH_B; ++i) {
+            double v = 0.0;
+            if (i >= c) {
+                v = i == c ? 1.0 : 0.0;
+                for (int k = c; k < i; ++k) v -= S[i][k] * X[k][c];
+                v /= S[i][i];
+            }
+            X[i][c] = v;
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < CH_B * CH_B; e += 256) {
+        const int i = e >> 6, c = e & 63;
+        L[toff + (size_t)i * n + c] = c <= i ? S[i][c] : 0.0;
+        invL[e] = X[i][c];
+        invLt[c * CH_B + i] = X[i][c];
+    }
+}
+
+// zero above the diagonal blocks of L [n][n] (the blocks on the diagonal are already lower triangular)
+__global__ __launch_bounds__(256) void k_zero_upper_blocks(double *__restrict__ L, int n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)n * n) return;
+    const int row = (int)(i / n), col = (int)(i % n);
+    if (col / CH_B > row / CH_B) L[i] = 0.0;
 }
 
 // ---------------------------------------------------------------------------
