@@ -617,7 +617,8 @@ def calibrate(a):
 
 def whiten(a):
     """Offline predictor build with data whitening (Alg. 1) of one layer's gate matrix on the GPU
-    (svdp_whiten_factors: fp64 MFMA contractions + two Jacobi eigen-decompositions).  One JSON line."""
+    (svdp_whiten_factors: fp64 MFMA contractions, blocked Cholesky factor, block-Jacobi eigen-decomposition).
+    One JSON line."""
     import numpy as np
     import torch
 
@@ -644,6 +645,12 @@ def whiten(a):
     err = torch.linalg.norm((W64 - Q.double() @ P.double().T) @ X64.T).item()
     ref = torch.linalg.norm(W64 @ X64.T).item()
     flops = 2.0 * (sp.d * sp.d * T + 2.0 * sp.D * sp.d * sp.d + sp.D * sp.d * r + sp.d * sp.d * r)
+    # block Jacobi: per round every 64 x 64 tile of the matrix takes two 64^3 products and every tile of the
+    # eigenvector rows one; d/32 - 1 rounds per sweep; the Cholesky factor d^3 / 3
+    tiles = (sp.d // 64) ** 2
+    jacobi_flops = sweeps[1] * (sp.d // 32 - 1) * tiles * 3 * 2.0 * 64 ** 3
+    all_flops = flops + jacobi_flops + sp.d ** 3 / 3.0
+    peak = 78.6
     cpu = None
     if not a.no_cpu_baseline:
         from oracle import calib
@@ -663,7 +670,11 @@ def whiten(a):
         "config": {"workload": f"{sp.name} gate matrix d={sp.d} D={sp.D}, rank {r}, {T} calibration tokens"},
         "jacobi_sweeps": list(sweeps), "sigma_first_last": [float(sigma[0]), float(sigma[-1])],
         "error_on_the_tokens": err, "error_relative_to_W_X": err / ref,
-        "contraction_gflop": flops / 1e9,
+        "contraction_gflop": flops / 1e9, "jacobi_gflop": jacobi_flops / 1e9,
+        "roofline": {"bound": "mfma", "achieved": all_flops / (ms * 1e-3) / 1e12, "peak": peak, "unit": "TFLOP/s",
+                     "frac": all_flops / (ms * 1e-3) / 1e12 / peak, "traffic": None,
+                     "kernel": "the whole call (fp64 matrix-core flops of the contractions, the Cholesky factor and the "
+                               "block-Jacobi tile updates over the wall time, host synchronisations included)"},
         "cpu_baseline": cpu}))
 
 
