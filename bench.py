@@ -174,7 +174,7 @@ def cpu_baseline_layer(layer, X, B, seconds):
 def machine_floor(torch, np):
     """Fixed costs and ceilings of this machine, measured with libsvdp_probe in the same process: cost of a
     dependent kernel node in a replayed graph, of handing one value from a node to the next, latency of a
-    dependent load at three footprints, and the streaming-read ceiling at two sizes."""
+    dependent load at three footprints, and the streaming-read ceiling at three sizes."""
     from paper_2603_14110_amd import probe
 
     probe.lib()
@@ -213,7 +213,7 @@ def machine_floor(torch, np):
     buf.fill_(1)
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     ceil = {}
-    for name, nbytes in (("32MB", 32 << 20), ("256MB", 256 << 20)):
+    for name, nbytes in (("32MB", 32 << 20), ("256MB", 256 << 20), ("2GB", 2 << 30)):
         nl = min((2 << 30) // nbytes, 32)
         views = [buf[i * nbytes:(i + 1) * nbytes] for i in range(nl)]     # a fresh region per launch
         ms, _ = time_graph(torch, lambda k: probe.stream_read(views[k], nbytes, 1024, sink), nl, 2, 3)

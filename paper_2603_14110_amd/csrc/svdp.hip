@@ -363,52 +363,49 @@ bool prepare_rows(const svdp_layer *L)
     return grant_lds<k_rows<W, NB, MODE>>(p.lds);
 }
 
-// The row kernel (gate, up, partial down projection per block) without the sum of the partials.
-template <typename W, int NB, int MODE>
-svdp_status launch_rows_only(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
-                             const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w,
-                             hipStream_t st)
-{
-    const RowsPlan p = plan_rows<W, NB>(L);
-    const int d = L->d, D = L->D;
-    const W *Wg = static_cast<const W *>(L->W_gate), *Wu = static_cast<const W *>(L->W_up);
-    const W *Wd = static_cast<const W *>(L->W_downT), *xs = static_cast<const W *>(x);
-    if (p.kind == ROWS_SEQ) {
-        hipLaunchKernelGGL((k_rows_seq<W, NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs, B,
-                           d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags,
-                           w.ypart);
-        return hip_status(hipSuccess);
-    }
-    if constexpr (std::is_same<W, bf16>::value) {
-        if (p.kind == ROWS_MATRIX) {
-            float *hbuf = reinterpret_cast<float *>(reinterpret_cast<char *>(w.ypart) + split_h_offset(d, NB));
-            int32_t *lst = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(w.ypart) + split_list_offset(d, D, NB));
-            hipLaunchKernelGGL((k_gate_up_mfma<NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, xs, B,
-                               d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags,
-                               hbuf, lst);
-            hipLaunchKernelGGL((k_down_slices<NB, MODE == ROWS_DENSE>), dim3(d / DS_SW, DOWN_RG), dim3(DS_THREADS), 0, st,
-                               Wd, lst, MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, d, hbuf, DOWN_MIN_CHUNK, w.ypart);
-            return hip_status(hipSuccess);
-        }
-    }
-    hipLaunchKernelGGL((k_rows<W, NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs, B, d, D,
-                       mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags, w.ypart);
-    return hip_status(hipSuccess);
-}
-
+// Gate, up and down over the list.  With y == nullptr the final sum of the partial results is left out (they
+// stay in the workspace): the row work by itself, for timing.
 template <typename W, int NB, int MODE>
 svdp_status launch_rows(const svdp_layer *L, const void *x, int B, const uint64_t *mask, const int32_t *idx_in,
                         const int32_t *nnz_in, int32_t *idx_out, int32_t *nnz_out, const Workspace &w, float *y,
                         hipStream_t st)
 {
-    const svdp_status s = launch_rows_only<W, NB, MODE>(L, x, B, mask, idx_in, nnz_in, idx_out, nnz_out, w, st);
-    if (s != SVDP_OK) return s;
     const RowsPlan p = plan_rows<W, NB>(L);
-    const int vpt = L->d / 4;
-    const int blocks = B * ((vpt + RED_COLS - 1) / RED_COLS);
-    hipLaunchKernelGGL(k_reduce_y, dim3(blocks), dim3(RED_COLS * RED_SEGS), 0, st, w.ypart,
-                       MODE == ROWS_DENSE ? nullptr : w.nnz, L->D, L->D, p.split ? DOWN_RG : ROWS_BLOCKS,
-                       p.split ? DOWN_MIN_CHUNK : p.min_chunk, NB, B, L->d, y);
+    const int d = L->d, D = L->D;
+    const W *Wg = static_cast<const W *>(L->W_gate), *Wu = static_cast<const W *>(L->W_up);
+    const W *Wd = static_cast<const W *>(L->W_downT), *xs = static_cast<const W *>(x);
+    bool matrix = false;
+    if constexpr (std::is_same<W, bf16>::value) {
+        matrix = p.kind == ROWS_MATRIX;
+        if (matrix) {
+            // gate/up kernel, then the down projection over column slices, which leaves DOWN_RG partial outputs
+            char *region = reinterpret_cast<char *>(w.ypart);
+            float *hbuf = reinterpret_cast<float *>(region + split_h_offset(d, NB));
+            int32_t *lst = reinterpret_cast<int32_t *>(region + split_list_offset(d, D, NB));
+            hipLaunchKernelGGL((k_gate_up_mfma<NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, xs, B,
+                               d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags,
+                               hbuf, lst);
+            hipLaunchKernelGGL((k_down_slices<NB, MODE == ROWS_DENSE>), dim3(d / DS_SW, DOWN_RG), dim3(DS_THREADS), 0, st,
+                               Wd, lst, MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, d, hbuf, DOWN_MIN_CHUNK, w.ypart);
+        }
+    }
+    if (matrix) {
+        // launched above
+    } else if (p.kind == ROWS_SEQ) {
+        hipLaunchKernelGGL((k_rows_seq<W, NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs, B,
+                           d, D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags,
+                           w.ypart);
+    } else {
+        hipLaunchKernelGGL((k_rows<W, NB, MODE>), dim3(ROWS_BLOCKS), dim3(ROWS_THREADS), p.lds, st, Wg, Wu, Wd, xs, B, d,
+                           D, mask, idx_in, nnz_in, idx_out, nnz_out, w.nnz, p.max_chunk, p.min_chunk, L->flags, w.ypart);
+    }
+    if (y != nullptr) {
+        const int vpt = d / 4;
+        const int blocks = B * ((vpt + RED_COLS - 1) / RED_COLS);
+        hipLaunchKernelGGL(k_reduce_y, dim3(blocks), dim3(RED_COLS * RED_SEGS), 0, st, w.ypart,
+                           MODE == ROWS_DENSE ? nullptr : w.nnz, D, D, p.split ? DOWN_RG : ROWS_BLOCKS,
+                           p.split ? DOWN_MIN_CHUNK : p.min_chunk, NB, B, d, y);
+    }
     return hip_status(hipSuccess);
 }
 
@@ -490,7 +487,7 @@ struct WhitenWs {
     double *A0, *A1;            // [d][d] symmetric matrix, ping-pong
     double *V0, *V1;            // [d][d] eigenvectors as rows, ping-pong
     double *St;                 // [d][d]  S^T, S = the lower Cholesky factor of X^T X
-    double *E;                  // [d][d]  S
+    double *S;                  // [d][d]  S
     double *lamG;               // [d] eigenvalues by place
     double *invL, *invLt;       // [64][64] scratch; [d/64][64][64] transposed inverses of S's diagonal blocks
     int32_t *fail;              // set by the factorisation if X^T X is not positive definite
@@ -521,7 +518,7 @@ WhitenWs carve_whiten(void *base, int d, int D, int T, int r)
     w.V0 = take(dd);
     w.V1 = take(dd);
     w.St = take(dd);
-    w.E = take(dd);
+    w.S = take(dd);
     w.lamG = take(d);
     w.invL = take(64 * 64);
     w.invLt = take((size_t)d * 64);
@@ -639,7 +636,7 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
         (void)hipGetLastError();
         return SVDP_ERR_HIP;
     }
-    cholesky_blocked(w.A0, w.E, w.A1, d, w.invL, w.invLt, w.sums, w.fail, st);
+    cholesky_blocked(w.A0, w.S, w.A1, d, w.invL, w.invLt, w.sums, w.fail, st);
     int32_t failed = 0;
     if (hipMemcpyAsync(&failed, w.fail, 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) {
@@ -648,7 +645,7 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
     }
     // S needs C positive definite (more independent tokens than dimensions)
     if (failed != 0) return SVDP_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (d + 31) / 32), dim3(256), 0, st, w.E, d, d, w.St);
+    hipLaunchKernelGGL((k_transpose_to_f64<double>), dim3((d + 31) / 32, (d + 31) / 32), dim3(256), 0, st, w.S, d, d, w.St);
 
     // M = W_gate S, G = M^T M
     hipLaunchKernelGGL((k_to_f64<W>), grid1((size_t)D * d), dim3(256), 0, st, Wg, (size_t)D * d, w.W64);
@@ -672,7 +669,7 @@ svdp_status whiten_impl(const void *W_gate, const void *X, int d, int D, int T, 
         return SVDP_ERR_HIP;
     }
     // Q = A = M V_r
-    hipLaunchKernelGGL(k_gather_rows, grid1((size_t)r * d), dim3(256), 0, st, V, w.sel, r, d, nullptr, w.Vr);
+    hipLaunchKernelGGL(k_gather_rows, grid1((size_t)r * d), dim3(256), 0, st, V, w.sel, r, d, w.Vr);
     dgemm_nt(w.M, d, w.Vr, d, w.out64, r, D, r, d, st);
     hipLaunchKernelGGL(k_f64_to_f32, grid1((size_t)D * r), dim3(256), 0, st, w.out64, (size_t)D * r, Q);
     // B = V_r^T S^-1 (block back-substitution; V_r^T is w.Vr, rows = the chosen eigenvectors), P = B^T
@@ -838,8 +835,6 @@ svdp_status svdp_active_rows(const svdp_layer *layer, const void *x, int32_t B, 
         constexpr int NB = decltype(nb)::value;
         if (!prepare_rows<W, NB, ROWS_MASK>(layer)) return SVDP_ERR_UNSUPPORTED;
         hipStream_t hs = static_cast<hipStream_t>(stream);
-        if (y == nullptr)
-            return launch_rows_only<W, NB, ROWS_MASK>(layer, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, hs);
         return launch_rows<W, NB, ROWS_MASK>(layer, x, B, mask, nullptr, nullptr, nullptr, nullptr, w, y, hs);
     });
 }

@@ -50,17 +50,13 @@ __global__ __launch_bounds__(256) void k_transpose_to_f64(const T *__restrict__ 
         if (c0 + y < cols && r0 + tx < rows) dst[(size_t)(c0 + y) * rows + r0 + tx] = tile[tx][y];
 }
 
-// dst[k][j] = src[idx[k]][j] * (colscale ? 1/sqrt(colscale[j]) : 1) for k < nsel
+// dst[k][j] = src[idx[k]][j] for k < nsel
 __global__ __launch_bounds__(256) void k_gather_rows(const double *__restrict__ src, const int32_t *__restrict__ idx,
-                                                     int nsel, int cols, const double *__restrict__ colscale,
-                                                     double *__restrict__ dst)
+                                                     int nsel, int cols, double *__restrict__ dst)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= (size_t)nsel * cols) return;
-    const int k = (int)(i / cols), j = (int)(i % cols);
-    double v = src[(size_t)idx[k] * cols + j];
-    if (colscale != nullptr) v /= sqrt(colscale[j]);
-    dst[i] = v;
+    dst[i] = src[(size_t)idx[i / cols] * cols + i % cols];
 }
 
 __global__ __launch_bounds__(256) void k_f64_to_f32(const double *__restrict__ src, size_t n, float *__restrict__ dst)
