@@ -24,8 +24,7 @@ namespace svdp {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
-constexpr int MF_ROWS = 16;      // list rows per phase-A tile
-constexpr int MF_TOK = 16;       // token slots of a tile (slots >= NB are padding)
+constexpr int MF_ROWS = 16;      // list rows per tile
 constexpr int MF_UA = 4;         // 64-element steps fetched together
 
 __device__ __forceinline__ f32x4_t mfma_bf16(const uint4 &a, const uint4 &b, f32x4_t c)
@@ -44,7 +43,7 @@ __global__ __launch_bounds__(ROWS_THREADS) void k_gate_up_mfma(
     static_assert(NB == 1 || NB == 2 || NB == 4 || NB == 8, "token slots are addressed with a mask");
     extern __shared__ uint4 smem16[];
     const int nvec = d / 8;                                        // 16-byte vectors per token
-    const int nsteps = d / 64;                                     // phase-A steps per row
+    const int nsteps = d / 64;                                     // 64-element steps per row
     uint4 *xs = smem16;                                            // [nsteps][2][4][NB], operand order
     float *part = reinterpret_cast<float *>(xs + NB * nvec);       // [ROWS_WAVES][tiles][2][16][NB]
     int *lidx = reinterpret_cast<int *>(part + (size_t)ROWS_WAVES * max_chunk * 2 * NB);
