@@ -74,6 +74,29 @@ def test_bench_sample_is_stratified_and_seeded():
     assert abs(dens[bench.stratified_sample(np, dens, 20)].mean() - dens.mean()) <= abs(first20 - dens.mean()) + 0.005
 
 
+def test_bench_attaches_measured_traffic_only_to_the_sample_it_was_measured_on():
+    """bench.py takes roofline.traffic from the committed counter summaries, and only for the workload, number of
+    steps and sampling seed a summary has an entry for (the driver's 20-step run and the default run among them)."""
+    import types
+
+    import bench
+
+    def args(**kw):
+        base = dict(workload="7b", batch=1, rank=0, flags=0, engine="auto", steps=20)
+        base.update(kw)
+        return types.SimpleNamespace(**base)
+
+    for a in (args(), args(steps=1024), args(workload="mistral", batch=8, steps=256)):
+        e = bench.measured_traffic(a)
+        assert e is not None and e["steps"] == a.steps and e["sample_seed"] == bench.SAMPLE_SEED
+        assert e["step_traffic"] >= e["step_algorithmic"] > 0
+        assert e["rows_traffic_per_launch"] >= e["rows_algorithmic_per_launch"] > 0
+        assert e["step_traffic"] < 1.5 * e["step_algorithmic"]
+    for a in (args(steps=21), args(workload="13b"), args(flags=2), args(engine="vector"), args(rank=128),
+              args(workload="mistral", batch=4, steps=256)):
+        assert bench.measured_traffic(a) is None
+
+
 def test_status_strings_and_version(svdp):
     L = svdp.lib()
     seen = {L.svdp_status_string(i).decode() for i in range(5)}
