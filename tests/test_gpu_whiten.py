@@ -1,8 +1,9 @@
 """GPU parity of the offline predictor build with data whitening (Alg. 1, svdp_whiten_factors) against the CPU
-oracle (oracle/calib.py: Cholesky factor, LAPACK SVD, triangular solve).  The factor pair is not unique (the
-library whitens with the symmetric eigen-factor, the oracle with the Cholesky factor as printed), so what is
-compared is what Alg. 1 defines: the product A B, the error on the data ||(W - A B) X^T||_F that it minimises,
-and the singular values of the whitened matrix."""
+oracle (oracle/calib.py: Cholesky factor, LAPACK SVD, triangular solve).  Both take the Cholesky factor the
+algorithm prints, so the pair is fixed up to the signs of the singular vectors (and rotations inside clusters of
+nearly equal singular values).  What is compared is what Alg. 1 defines - the product A B, the error on the data
+||(W - A B) X^T||_F that it minimises, the singular values of the whitened matrix - and, up to sign, the leading
+columns of the two factors themselves."""
 import numpy as np
 import pytest
 
@@ -61,6 +62,13 @@ def test_whitened_factors_against_oracle(env, d, D, T, r, dt, decay):
     sv_or = np.linalg.norm(A, axis=0)
     assert np.all(np.abs(sigma - sv_or) <= 1e-5 * sv_or[0]), np.abs(sigma - sv_or).max() / sv_or[0]
     assert np.all(np.diff(sigma) <= 1e-6 * sigma[0])
+    # the leading, well separated columns of the factors themselves, up to sign (Q = A, P = B^T)
+    for k in range(min(r, 3)):
+        if k + 1 < len(sv_or) and sv_or[k] - sv_or[k + 1] < 0.05 * sv_or[k]:
+            break
+        sgn = np.sign(np.dot(Q[:, k], A[:, k]))
+        assert np.linalg.norm(sgn * Q[:, k] - A[:, k]) <= 1e-4 * np.linalg.norm(A[:, k]), k
+        assert np.linalg.norm(sgn * P[:, k] - B[k, :]) <= 1e-4 * np.linalg.norm(B[k, :]), k
     # Q's columns are orthogonal with those norms (Q = U_r Sigma_r)
     G = Q.T @ Q
     assert np.linalg.norm(G - np.diag(np.diag(G))) <= 1e-5 * np.linalg.norm(G)
